@@ -1,0 +1,169 @@
+/*
+ * fedattn.h - C ABI of the FedAttn attention library for AMD MI355X (gfx950).
+ *
+ * Federated Attention runs the self-attention of a stack of M Transformer blocks
+ * over a global sequence that is partitioned among N participants (Section IV-A:
+ * disjoint ordered index sets L_n; here contiguous segments given by offsets).
+ * In a local block every participant attends only to its own tokens (Phase I,
+ * local self-attention); in every H-th block the participants' K and V are
+ * aggregated into a global KV matrix and each participant's queries attend to it
+ * (Phase II, global self-attention; Algorithm 1).  Decoding reuses the per-block
+ * KV caches kept from prefill (Section IV-C).
+ *
+ * Conventions for every entry point
+ *  - "device" pointers are HIP device memory on the current device; "host"
+ *    pointers are ordinary host memory, read before the call returns.
+ *  - Tensors are token-major and contiguous: q,out [tokens, Hq, D];
+ *    k,v [tokens, Hkv, D].  Element type is params->dtype.  Device tensor
+ *    pointers must be 16-byte aligned.
+ *  - The caller owns every buffer.  The library allocates no device memory and
+ *    keeps no state between calls.  Kernels are enqueued on `stream`
+ *    (a hipStream_t cast to void*, NULL = default stream) and the call returns
+ *    without waiting for them.
+ *  - Every failure is a return code; fedattn_last_error() gives the reason as
+ *    text (thread-local).  Nothing is enqueued when a call fails validation.
+ *  - Query head h reads KV head h / (Hq/Hkv) (grouped-query attention).
+ *  - Softmax runs on scores scaled by softmax_scale (0 selects 1/sqrt(D),
+ *    Section III-B), accumulates in fp32 and writes out in params->dtype.
+ *  - A query with no visible key gets a zero output row.
+ */
+#ifndef FEDATTN_H
+#define FEDATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FEDATTN_MAX_PARTICIPANTS 128
+
+typedef enum {
+  FEDATTN_OK = 0,
+  FEDATTN_EINVAL = 1,       /* bad argument: null/misaligned pointer, bad offsets, bad sizes */
+  FEDATTN_EUNSUPPORTED = 2, /* valid request the kernels do not cover */
+  FEDATTN_EWORKSPACE = 3,   /* workspace missing or smaller than fedattn_workspace_bytes() */
+  FEDATTN_ELAUNCH = 4       /* HIP reported an error when enqueuing */
+} fedattn_status;
+
+typedef enum { FEDATTN_BF16 = 0, FEDATTN_F32 = 1 } fedattn_dtype;
+
+typedef enum { FEDATTN_OP_PREFILL = 0, FEDATTN_OP_DECODE = 1 } fedattn_op;
+
+typedef struct fedattn_params {
+  int32_t n_participants; /* N, 1..FEDATTN_MAX_PARTICIPANTS */
+  int32_t n_q_heads;      /* Hq */
+  int32_t n_kv_heads;     /* Hkv, divides Hq */
+  int32_t head_dim;       /* D: multiple of 8, at most 256 (bf16 with D = 64 or 128 runs on MFMA) */
+  int32_t sync_interval;  /* H of Algorithm 1; <= 0: no block ever synchronises */
+  int32_t causal;         /* 1: decoder (a token sees itself and earlier tokens); 0: encoder */
+  int32_t dtype;          /* fedattn_dtype of q, k, v, out */
+  float softmax_scale;    /* 0: 1/sqrt(D) */
+} fedattn_params;
+
+/* Algorithm 1: with blocks numbered m = H t + h (1-based), block m runs global
+ * attention iff h = H.  For the 0-based block_idx used here that is
+ * H >= 1 && (block_idx + 1) % H == 0.  Returns 1 (sync block) or 0 (local). */
+int fedattn_is_sync_block(int32_t sync_interval, int32_t block_idx);
+
+/* Bytes of device workspace the given op needs (16-byte aligned start).
+ *   FEDATTN_OP_PREFILL: `tokens` = total tokens; needed only when a keep-list is
+ *     passed (chunk_tokens > 0); 0 otherwise.
+ *   FEDATTN_OP_DECODE:  `tokens` = total cache capacity; chunk_tokens ignored.
+ * Returns 0 on invalid params. */
+size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t tokens,
+                               int32_t chunk_tokens);
+
+/*
+ * Attention of one Transformer block over all participants' tokens (prefill).
+ *   Local block (Phase I, o_n = Attention(q_n, k_n, v_n)): query i sees keys of
+ *   its own segment only.  Sync block (Phase II, o_n = Attention(q_n, K, V)):
+ *   query i sees the aggregated KV of all participants in the order of the
+ *   global sequence.  With causal = 1 a query sees key j only if j <= i.
+ *   Sparse KV exchange (adaptive KV aggregation): when keep_chunks is given,
+ *   a sync block sees a remote participant's rows only in the chunks flagged 1;
+ *   a participant's own rows are always complete.
+ *
+ *   block_idx      0-based block index; with sync_override = -1 the block is a sync
+ *                  block iff fedattn_is_sync_block(params->sync_interval, block_idx).
+ *   q,k,v,out      device; q,out [total,Hq,D], k,v [total,Hkv,D]; k,v hold the
+ *                  aggregated (global-order) matrices, see fedattn_aggregate_kv.
+ *   seg_offsets    host int32[N+1], non-decreasing, [0] = 0, [N] = total tokens.
+ *                  Empty segments are legal.
+ *   keep_chunks    device uint8[sum_n ceil(len_n / chunk_tokens)] or NULL (dense).
+ *                  Chunk c of participant n covers tokens
+ *                  seg_offsets[n] + c*chunk_tokens ... (clipped to the segment);
+ *                  flags are stored participant after participant.  Read only in
+ *                  sync blocks.  chunk_tokens must be a positive multiple of 64
+ *                  when keep_chunks is given.
+ *   sync_override  -1: rule above; 0: force local; 1: force sync (variable sync
+ *                  schedules H_t).
+ *   workspace      device, >= fedattn_workspace_bytes(PREFILL); may be NULL when
+ *                  keep_chunks is NULL.
+ */
+fedattn_status fedattn_prefill(const fedattn_params* params, int32_t block_idx, const void* q,
+                               const void* k, const void* v, void* out,
+                               const int32_t* seg_offsets, const uint8_t* keep_chunks,
+                               int32_t chunk_tokens, int32_t sync_override, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/*
+ * The same for n_blocks consecutive blocks block_idx0 .. block_idx0+n_blocks-1 in
+ * one launch.  Block b reads q + b*q_block_stride elements etc. (strides in
+ * elements, multiples of 8); every block uses the same segment layout; dense
+ * exchange only.  Semantics per block are exactly those of fedattn_prefill.  For
+ * workloads whose per-block work is too small to fill the GPU.
+ */
+fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t block_idx0,
+                                      int32_t n_blocks, const void* q, const void* k,
+                                      const void* v, void* out, int64_t q_block_stride,
+                                      int64_t kv_block_stride, const int32_t* seg_offsets,
+                                      void* stream);
+
+/*
+ * One decoding step of one block (Section IV-C): one new query per participant
+ * over the block's KV cache.  The caller has already appended the step's own
+ * k,v, so a query sees itself; everything cached is in the past (no mask).
+ *   Local block: participant n's query sees rows [0, seg_lens[n]) of its own
+ *   cache segment.  Sync block: it also sees rows [0, remote_lens[m]) of every
+ *   other participant m's segment (the aggregated cache).
+ *
+ *   q,out          device [N,Hq,D].
+ *   k_cache,v_cache device [capacity_total,Hkv,D].
+ *   seg_offsets    host int32[N+1]: capacity layout ([0] = 0, [N] = capacity_total).
+ *   seg_lens       host int32[N]: valid rows of each segment, <= its capacity.
+ *   remote_lens    host int32[N] or NULL (= seg_lens): rows of segment m that the
+ *                  other participants see in a sync block (e.g. the prompt length
+ *                  when generated tokens are not exchanged).
+ *   workspace      device, >= fedattn_workspace_bytes(DECODE); holds split-KV partials.
+ */
+fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q,
+                              const void* k_cache, const void* v_cache, void* out,
+                              const int32_t* seg_offsets, const int32_t* seg_lens,
+                              const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/*
+ * KV aggregation of a sync block (Phase II): [K V] = sum_n Pi_n [k_n v_n], i.e.
+ * row r of participant n's local k_n, v_n lands at global row seg_offsets[n] + r.
+ *   k_local,v_local host arrays of N device pointers, entry n -> [len_n,Hkv,D]
+ *                   (entries of empty segments may be NULL).
+ *   k_global,v_global device [total,Hkv,D], written completely.
+ * A pure copy; on one GPU a caller that already keeps the participants' K,V
+ * back to back in global order can skip it.
+ */
+fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* const* k_local,
+                                    const void* const* v_local, const int32_t* seg_offsets,
+                                    void* k_global, void* v_global, void* stream);
+
+/* Reason of the calling thread's most recent failure ("" if none). */
+const char* fedattn_last_error(void);
+
+/* Library version string. */
+const char* fedattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FEDATTN_H */

@@ -1,0 +1,192 @@
+"""Python binding of the FedAttn HIP library (argument marshalling only).
+
+Every function has the name and the meaning of the C entry point it calls
+(include/fedattn.h); all arithmetic runs in the library's gfx950 kernels.
+PyTorch is used for device memory and the stream only.  There is no CPU or
+PyTorch fallback: if libfedattn.so is missing or fails to load, importing a
+function's result fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfedattn.so")
+
+FEDATTN_OK, FEDATTN_EINVAL, FEDATTN_EUNSUPPORTED, FEDATTN_EWORKSPACE, FEDATTN_ELAUNCH = range(5)
+FEDATTN_BF16, FEDATTN_F32 = 0, 1
+FEDATTN_OP_PREFILL, FEDATTN_OP_DECODE = 0, 1
+FEDATTN_MAX_PARTICIPANTS = 128
+
+EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill",
+           "fedattn_prefill_blocks", "fedattn_decode", "fedattn_aggregate_kv",
+           "fedattn_last_error", "fedattn_version")
+
+
+class fedattn_params(ctypes.Structure):
+    _fields_ = [("n_participants", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("sync_interval", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+
+
+class FedAttnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("fedattn status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load libfedattn.so (built by paper_2511_02647_amd.build.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s not found: build it with `python -m paper_2511_02647_amd.build` "
+                           "(there is no fallback path)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, i64, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    pp = ctypes.POINTER(fedattn_params)
+    lib.fedattn_is_sync_block.argtypes = [i32, i32]
+    lib.fedattn_is_sync_block.restype = ctypes.c_int
+    lib.fedattn_workspace_bytes.argtypes = [pp, i32, i32, i32]
+    lib.fedattn_workspace_bytes.restype = sz
+    lib.fedattn_prefill.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+    lib.fedattn_prefill.restype = ctypes.c_int
+    lib.fedattn_prefill_blocks.argtypes = [pp, i32, i32, vp, vp, vp, vp, i64, i64, vp, vp]
+    lib.fedattn_prefill_blocks.restype = ctypes.c_int
+    lib.fedattn_decode.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.fedattn_decode.restype = ctypes.c_int
+    lib.fedattn_aggregate_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp]
+    lib.fedattn_aggregate_kv.restype = ctypes.c_int
+    lib.fedattn_last_error.restype = ctypes.c_char_p
+    lib.fedattn_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def make_params(n_participants: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                sync_interval: int, dtype: torch.dtype, causal: bool = True,
+                softmax_scale: float = 0.0) -> fedattn_params:
+    if dtype == torch.bfloat16:
+        dt = FEDATTN_BF16
+    elif dtype == torch.float32:
+        dt = FEDATTN_F32
+    else:
+        raise TypeError("dtype must be torch.bfloat16 or torch.float32")
+    return fedattn_params(n_participants, n_q_heads, n_kv_heads, head_dim, sync_interval,
+                          1 if causal else 0, dt, float(softmax_scale))
+
+
+def _check(status: int) -> None:
+    if status != FEDATTN_OK:
+        raise FedAttnError(status, load().fedattn_last_error().decode())
+
+
+def _dev(t: Optional[torch.Tensor], name: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("%s must be a device tensor" % name)
+    if not t.is_contiguous():
+        raise TypeError("%s must be contiguous" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _host_i32(a, name: str) -> np.ndarray:
+    arr = np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+    if arr.ndim != 1:
+        raise TypeError("%s must be one-dimensional" % name)
+    return arr
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def fedattn_version() -> str:
+    return load().fedattn_version().decode()
+
+
+def fedattn_is_sync_block(sync_interval: int, block_idx: int) -> bool:
+    return bool(load().fedattn_is_sync_block(int(sync_interval), int(block_idx)))
+
+
+def fedattn_workspace_bytes(params: fedattn_params, op: int, tokens: int, chunk_tokens: int = 0) -> int:
+    return int(load().fedattn_workspace_bytes(ctypes.byref(params), int(op), int(tokens), int(chunk_tokens)))
+
+
+def fedattn_prefill(params: fedattn_params, block_idx: int, q: torch.Tensor, k: torch.Tensor,
+                    v: torch.Tensor, out: torch.Tensor, seg_offsets, keep_chunks: Optional[torch.Tensor] = None,
+                    chunk_tokens: int = 0, sync_override: int = -1,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    if seg.shape[0] != params.n_participants + 1:
+        raise ValueError("seg_offsets must have n_participants + 1 entries")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().fedattn_prefill(ctypes.byref(params), int(block_idx), _dev(q, "q"), _dev(k, "k"),
+                                  _dev(v, "v"), _dev(out, "out"), seg.ctypes.data_as(ctypes.c_void_p),
+                                  _dev(keep_chunks, "keep_chunks"), int(chunk_tokens), int(sync_override),
+                                  _dev(workspace, "workspace"), ws_bytes, _stream(stream)))
+
+
+def fedattn_prefill_blocks(params: fedattn_params, block_idx0: int, n_blocks: int, q: torch.Tensor,
+                           k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, q_block_stride: int,
+                           kv_block_stride: int, seg_offsets, stream=None) -> None:
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    if seg.shape[0] != params.n_participants + 1:
+        raise ValueError("seg_offsets must have n_participants + 1 entries")
+    _check(load().fedattn_prefill_blocks(ctypes.byref(params), int(block_idx0), int(n_blocks), _dev(q, "q"),
+                                         _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), int(q_block_stride),
+                                         int(kv_block_stride), seg.ctypes.data_as(ctypes.c_void_p),
+                                         _stream(stream)))
+
+
+def fedattn_decode(params: fedattn_params, block_idx: int, q: torch.Tensor, k_cache: torch.Tensor,
+                   v_cache: torch.Tensor, out: torch.Tensor, seg_offsets, seg_lens, remote_lens=None,
+                   sync_override: int = -1, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    lens = _host_i32(seg_lens, "seg_lens")
+    if seg.shape[0] != params.n_participants + 1 or lens.shape[0] != params.n_participants:
+        raise ValueError("seg_offsets / seg_lens have the wrong length")
+    rl = None
+    if remote_lens is not None:
+        rl = _host_i32(remote_lens, "remote_lens")
+        if rl.shape[0] != params.n_participants:
+            raise ValueError("remote_lens has the wrong length")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().fedattn_decode(ctypes.byref(params), int(block_idx), _dev(q, "q"), _dev(k_cache, "k_cache"),
+                                 _dev(v_cache, "v_cache"), _dev(out, "out"),
+                                 seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
+                                 None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
+                                 int(sync_override), _dev(workspace, "workspace"), ws_bytes, _stream(stream)))
+
+
+def fedattn_aggregate_kv(params: fedattn_params, k_local: Sequence[Optional[torch.Tensor]],
+                         v_local: Sequence[Optional[torch.Tensor]], seg_offsets, k_global: torch.Tensor,
+                         v_global: torch.Tensor, stream=None) -> None:
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    n = params.n_participants
+    if seg.shape[0] != n + 1 or len(k_local) != n or len(v_local) != n:
+        raise ValueError("k_local / v_local / seg_offsets have the wrong length")
+    kp = (ctypes.c_void_p * n)()
+    vp = (ctypes.c_void_p * n)()
+    for i in range(n):
+        for arr, t, nm in ((kp, k_local[i], "k_local"), (vp, v_local[i], "v_local")):
+            if t is None or t.numel() == 0:
+                arr[i] = None
+            else:
+                if not (t.is_cuda and t.is_contiguous()):
+                    raise TypeError("%s[%d] must be a contiguous device tensor" % (nm, i))
+                arr[i] = t.data_ptr()
+    _check(load().fedattn_aggregate_kv(ctypes.byref(params), kp, vp, seg.ctypes.data_as(ctypes.c_void_p),
+                                       _dev(k_global, "k_global"), _dev(v_global, "v_global"), _stream(stream)))

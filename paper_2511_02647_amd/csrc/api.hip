@@ -1,0 +1,321 @@
+// C ABI of the FedAttn library: argument validation, the sync-block rule of
+// Algorithm 1, kernel selection and launch.  No device memory is allocated here
+// and nothing is kept between calls.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "common.h"
+
+using namespace fedattn;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+fedattn_status fail(fedattn_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+fedattn_status check_params(const fedattn_params* p) {
+  if (!p) return fail(FEDATTN_EINVAL, "params is NULL");
+  if (p->n_participants < 1 || p->n_participants > FEDATTN_MAX_PARTICIPANTS)
+    return fail(FEDATTN_EINVAL, "n_participants %d outside 1..%d", p->n_participants, FEDATTN_MAX_PARTICIPANTS);
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads != 0)
+    return fail(FEDATTN_EINVAL, "n_q_heads %d must be a positive multiple of n_kv_heads %d", p->n_q_heads,
+                p->n_kv_heads);
+  if (p->head_dim < 8 || p->head_dim > 256 || p->head_dim % 8 != 0)
+    return fail(FEDATTN_EINVAL, "head_dim %d must be a multiple of 8 in 8..256", p->head_dim);
+  if (p->dtype != FEDATTN_BF16 && p->dtype != FEDATTN_F32) return fail(FEDATTN_EINVAL, "unknown dtype %d", p->dtype);
+  if (!(p->softmax_scale >= 0.f) || !isfinite(p->softmax_scale))
+    return fail(FEDATTN_EINVAL, "softmax_scale must be finite and >= 0");
+  if (p->causal != 0 && p->causal != 1) return fail(FEDATTN_EINVAL, "causal must be 0 or 1");
+  return FEDATTN_OK;
+}
+
+float resolve_scale(const fedattn_params* p) {
+  return p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+}
+
+fedattn_status check_offsets(const fedattn_params* p, const int32_t* seg) {
+  if (!seg) return fail(FEDATTN_EINVAL, "seg_offsets is NULL");
+  if (seg[0] != 0) return fail(FEDATTN_EINVAL, "seg_offsets[0] must be 0");
+  for (int n = 0; n < p->n_participants; ++n)
+    if (seg[n + 1] < seg[n]) return fail(FEDATTN_EINVAL, "seg_offsets decreases at participant %d", n);
+  return FEDATTN_OK;
+}
+
+bool use_mfma_prefill(const fedattn_params* p, bool has_keep, int chunk_tokens) {
+  if (p->dtype != FEDATTN_BF16) return false;
+  if (p->head_dim != 64 && p->head_dim != 128) return false;
+  if (has_keep && chunk_tokens % kKvTile != 0) return false;
+  return true;
+}
+
+int env_int(const char* name, int dflt) {
+  const char* s = getenv(name);
+  if (!s || !*s) return dflt;
+  const int v = atoi(s);
+  return v > 0 ? v : dflt;
+}
+
+// cache rows per decode workgroup (multiples of 128: 4 wavefronts x 32 rows)
+int decode_chunk_rows(bool sync) {
+  static const int local_rows = (env_int("FEDATTN_DECODE_CHUNK_LOCAL", 256) + 127) / 128 * 128;
+  static const int sync_rows = (env_int("FEDATTN_DECODE_CHUNK_SYNC", 512) + 127) / 128 * 128;
+  return sync ? sync_rows : local_rows;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// prefill workspace: [kept_cum: (kMaxP+1) int32, padded][kept_tiles: int2 per 64-row tile]
+constexpr size_t kKeptCumBytes = 1024;
+size_t prefill_ws_bytes(const fedattn_params* p, int32_t tokens) {
+  const size_t max_tiles = (size_t)tokens / kKvTile + (size_t)p->n_participants + 1;
+  return kKeptCumBytes + align_up(max_tiles * sizeof(int2), 16);
+}
+
+size_t decode_ws_bytes(const fedattn_params* p, int32_t capacity) {
+  if (!(p->dtype == FEDATTN_BF16 && (p->head_dim == 64 || p->head_dim == 128))) return 16;
+  const size_t G = (size_t)(p->n_q_heads / p->n_kv_heads);
+  const size_t N = (size_t)p->n_participants;
+  const size_t ch_local = (size_t)capacity / decode_chunk_rows(false) + N;
+  const size_t ch_sync = (size_t)capacity / decode_chunk_rows(true) + N;
+  const size_t rows_local = (size_t)p->n_kv_heads * ch_local * G;
+  const size_t rows_sync = (size_t)p->n_kv_heads * ch_sync * G * N;
+  const size_t rows = rows_local > rows_sync ? rows_local : rows_sync;
+  return align_up(rows * (size_t)p->head_dim * 4, 256) + align_up(rows * 8, 256);
+}
+
+fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t n_blocks, const void* q,
+                           const void* k, const void* v, void* out, int64_t q_stride, int64_t kv_stride,
+                           const int32_t* seg, const uint8_t* keep_chunks, int32_t chunk_tokens,
+                           int32_t sync_override, void* workspace, size_t workspace_bytes, void* stream) {
+  fedattn_status st = check_params(p);
+  if (st != FEDATTN_OK) return st;
+  st = check_offsets(p, seg);
+  if (st != FEDATTN_OK) return st;
+  if (block_idx0 < 0 || n_blocks < 0) return fail(FEDATTN_EINVAL, "negative block index or count");
+  if (sync_override < -1 || sync_override > 1) return fail(FEDATTN_EINVAL, "sync_override must be -1, 0 or 1");
+  const int N = p->n_participants;
+  const int32_t total = seg[N];
+  if (total == 0 || n_blocks == 0) return FEDATTN_OK;
+  if (!q || !k || !v || !out) return fail(FEDATTN_EINVAL, "q, k, v and out must not be NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(FEDATTN_EINVAL, "q, k, v and out must be 16-byte aligned");
+  if (n_blocks > 1 && (q_stride % 8 != 0 || kv_stride % 8 != 0 || q_stride < 0 || kv_stride < 0))
+    return fail(FEDATTN_EINVAL, "block strides must be non-negative multiples of 8 elements");
+  if (n_blocks > 65535) return fail(FEDATTN_EINVAL, "at most 65535 blocks per launch");
+  const bool has_keep = keep_chunks != nullptr;
+  if (has_keep && chunk_tokens <= 0) return fail(FEDATTN_EINVAL, "chunk_tokens must be positive with a keep-list");
+
+  PrefillArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = q; a.k = k; a.v = v; a.out = out;
+  a.q_block_stride = q_stride;
+  a.kv_block_stride = kv_stride;
+  a.keep_chunks = keep_chunks;
+  a.chunk_tokens = has_keep ? chunk_tokens : 1;
+  a.total = total;
+  a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.D = p->head_dim;
+  a.block_idx0 = block_idx0;
+  a.sync_interval = p->sync_interval;
+  a.sync_override = sync_override;
+  a.causal = p->causal;
+  a.scale = resolve_scale(p);
+  a.seg.n = N;
+
+  const bool mfma = use_mfma_prefill(p, has_keep, chunk_tokens);
+  const int G = a.Hq / a.Hkv;
+  a.heads_per_wg = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
+  a.q_tile_rows = kWaveRows * (4 / a.heads_per_wg);
+  int64_t tiles = 0, chunks = 0;
+  for (int n = 0; n <= N; ++n) {
+    a.seg.seg_off[n] = seg[n];
+    a.seg.tile_cum[n] = (int32_t)tiles;
+    a.seg.chunk_cum[n] = (int32_t)chunks;
+    if (n < N) {
+      const int64_t len = seg[n + 1] - seg[n];
+      tiles += (len + a.q_tile_rows - 1) / a.q_tile_rows;
+      if (has_keep) chunks += (len + chunk_tokens - 1) / chunk_tokens;
+    }
+  }
+  a.n_q_tiles = (int32_t)tiles;
+  if (tiles * a.Hkv * (G / a.heads_per_wg) > 0x7fffffffLL) return fail(FEDATTN_EUNSUPPORTED, "too many query tiles");
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  // a block reads the keep-list only if it is a sync block
+  bool any_sync = sync_override == 1;
+  if (sync_override == -1)
+    for (int b = 0; b < n_blocks && !any_sync; ++b) any_sync = sync_block_rule(p->sync_interval, block_idx0 + b);
+  if (!has_keep || !any_sync) a.keep_chunks = nullptr;
+
+  if (mfma) {
+    if (a.keep_chunks) {
+      const size_t need = prefill_ws_bytes(p, total);
+      if (!workspace || workspace_bytes < need)
+        return fail(FEDATTN_EWORKSPACE, "prefill with a keep-list needs %zu workspace bytes, got %zu", need,
+                    workspace_bytes);
+      if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
+      int32_t* kept_cum = reinterpret_cast<int32_t*>(workspace);
+      int2* kept_tiles = reinterpret_cast<int2*>(reinterpret_cast<unsigned char*>(workspace) + kKeptCumBytes);
+      a.kept_cum = kept_cum;
+      a.kept_tiles = kept_tiles;
+      hipError_t e = launch_build_kept_tiles(a, kept_tiles, kept_cum, s);
+      if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "keep-list compaction: %s", hipGetErrorString(e));
+    }
+    hipError_t e = launch_prefill_mfma(a, n_blocks, s);
+    if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "prefill (mfma): %s", hipGetErrorString(e));
+  } else {
+    hipError_t e = launch_prefill_generic(a, n_blocks, p->dtype, s);
+    if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "prefill (general): %s", hipGetErrorString(e));
+  }
+  return FEDATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fedattn_is_sync_block(int32_t sync_interval, int32_t block_idx) {
+  return sync_block_rule(sync_interval, block_idx) ? 1 : 0;
+}
+
+size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t tokens, int32_t chunk_tokens) {
+  if (check_params(params) != FEDATTN_OK || tokens < 0) return 0;
+  if (op == FEDATTN_OP_PREFILL) return chunk_tokens > 0 ? prefill_ws_bytes(params, tokens) : 0;
+  if (op == FEDATTN_OP_DECODE) return decode_ws_bytes(params, tokens);
+  fail(FEDATTN_EINVAL, "unknown op %d", op);
+  return 0;
+}
+
+fedattn_status fedattn_prefill(const fedattn_params* params, int32_t block_idx, const void* q, const void* k,
+                               const void* v, void* out, const int32_t* seg_offsets, const uint8_t* keep_chunks,
+                               int32_t chunk_tokens, int32_t sync_override, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  return run_prefill(params, block_idx, 1, q, k, v, out, 0, 0, seg_offsets, keep_chunks, chunk_tokens,
+                     sync_override, workspace, workspace_bytes, stream);
+}
+
+fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                      const void* q, const void* k, const void* v, void* out,
+                                      int64_t q_block_stride, int64_t kv_block_stride,
+                                      const int32_t* seg_offsets, void* stream) {
+  return run_prefill(params, block_idx0, n_blocks, q, k, v, out, q_block_stride, kv_block_stride, seg_offsets,
+                     nullptr, 0, -1, nullptr, 0, stream);
+}
+
+fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, const int32_t* seg_offsets, const int32_t* seg_lens,
+                              const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  fedattn_status st = check_params(params);
+  if (st != FEDATTN_OK) return st;
+  st = check_offsets(params, seg_offsets);
+  if (st != FEDATTN_OK) return st;
+  if (!seg_lens) return fail(FEDATTN_EINVAL, "seg_lens is NULL");
+  if (block_idx < 0) return fail(FEDATTN_EINVAL, "negative block index");
+  if (sync_override < -1 || sync_override > 1) return fail(FEDATTN_EINVAL, "sync_override must be -1, 0 or 1");
+  const int N = params->n_participants;
+  for (int n = 0; n < N; ++n) {
+    const int cap = seg_offsets[n + 1] - seg_offsets[n];
+    if (seg_lens[n] < 0 || seg_lens[n] > cap)
+      return fail(FEDATTN_EINVAL, "seg_lens[%d] = %d outside 0..capacity %d", n, seg_lens[n], cap);
+    if (remote_lens && (remote_lens[n] < 0 || remote_lens[n] > cap))
+      return fail(FEDATTN_EINVAL, "remote_lens[%d] = %d outside 0..capacity %d", n, remote_lens[n], cap);
+  }
+  if (!q || !out) return fail(FEDATTN_EINVAL, "q and out must not be NULL");
+  const int32_t capacity = seg_offsets[N];
+  if (capacity > 0 && (!k_cache || !v_cache)) return fail(FEDATTN_EINVAL, "k_cache and v_cache must not be NULL");
+  if (!aligned16(q) || !aligned16(out) || !aligned16(k_cache) || !aligned16(v_cache))
+    return fail(FEDATTN_EINVAL, "q, out, k_cache and v_cache must be 16-byte aligned");
+
+  DecodeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.out = out;
+  a.N = N; a.Hq = params->n_q_heads; a.Hkv = params->n_kv_heads; a.D = params->head_dim;
+  const bool sync = sync_override >= 0 ? sync_override != 0 : sync_block_rule(params->sync_interval, block_idx);
+  a.is_sync = sync ? 1 : 0;
+  a.has_remote = (sync && remote_lens) ? 1 : 0;
+  a.scale = resolve_scale(params);
+  const int G = a.Hq / a.Hkv;
+  a.cols = sync ? N * G : G;
+  a.chunk_rows = decode_chunk_rows(sync);
+  int64_t chunks = 0;
+  for (int n = 0; n <= N; ++n) {
+    a.seg_off[n] = seg_offsets[n];
+    a.chunk_cum[n] = (int32_t)chunks;
+    if (n < N) {
+      a.seg_lens[n] = seg_lens[n];
+      a.remote_lens[n] = remote_lens ? remote_lens[n] : seg_lens[n];
+      const int rem = a.has_remote ? a.remote_lens[n] : seg_lens[n];
+      const int rows = sync ? (seg_lens[n] > rem ? seg_lens[n] : rem) : seg_lens[n];
+      chunks += (rows + a.chunk_rows - 1) / a.chunk_rows;
+    }
+  }
+  a.n_chunks = (int32_t)chunks;
+
+  const bool mfma = params->dtype == FEDATTN_BF16 && (a.D == 64 || a.D == 128);
+  if (mfma) {
+    const size_t need = decode_ws_bytes(params, capacity);
+    if (!workspace || workspace_bytes < need)
+      return fail(FEDATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need, workspace_bytes);
+    if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
+    const size_t rows = (size_t)a.Hkv * (size_t)a.n_chunks * (size_t)a.cols;
+    const size_t o_bytes = align_up(rows * (size_t)a.D * 4, 256);
+    if (o_bytes + rows * 8 > workspace_bytes)
+      return fail(FEDATTN_EWORKSPACE, "decode partials (%zu bytes) exceed the workspace", o_bytes + rows * 8);
+    a.part_o = reinterpret_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + o_bytes);
+  }
+  hipError_t e = launch_decode(a, params->dtype, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
+fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* const* k_local,
+                                    const void* const* v_local, const int32_t* seg_offsets, void* k_global,
+                                    void* v_global, void* stream) {
+  fedattn_status st = check_params(params);
+  if (st != FEDATTN_OK) return st;
+  st = check_offsets(params, seg_offsets);
+  if (st != FEDATTN_OK) return st;
+  if (!k_local || !v_local) return fail(FEDATTN_EINVAL, "k_local and v_local must not be NULL");
+  const int N = params->n_participants;
+  if (seg_offsets[N] == 0) return FEDATTN_OK;
+  if (!k_global || !v_global || !aligned16(k_global) || !aligned16(v_global))
+    return fail(FEDATTN_EINVAL, "k_global and v_global must be non-NULL and 16-byte aligned");
+  AggregateArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n = N;
+  a.row_bytes = params->n_kv_heads * params->head_dim * (params->dtype == FEDATTN_BF16 ? 2 : 4);
+  a.k_global = k_global;
+  a.v_global = v_global;
+  for (int n = 0; n <= N; ++n) a.seg_off[n] = seg_offsets[n];
+  for (int n = 0; n < N; ++n) {
+    a.k_local[n] = k_local[n];
+    a.v_local[n] = v_local[n];
+    if (seg_offsets[n + 1] > seg_offsets[n]) {
+      if (!k_local[n] || !v_local[n]) return fail(FEDATTN_EINVAL, "local K/V of participant %d is NULL", n);
+      if (!aligned16(k_local[n]) || !aligned16(v_local[n]))
+        return fail(FEDATTN_EINVAL, "local K/V of participant %d is not 16-byte aligned", n);
+    }
+  }
+  hipError_t e = launch_aggregate(a, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "aggregate: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
+const char* fedattn_last_error(void) { return g_err; }
+
+const char* fedattn_version(void) { return "fedattn-gfx950 0.1"; }
+
+}  // extern "C"

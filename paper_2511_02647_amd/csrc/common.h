@@ -1,0 +1,121 @@
+// Shared declarations of the FedAttn HIP library (gfx950 only): kernel argument
+// blocks, launcher prototypes and small device helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fedattn.h"
+
+namespace fedattn {
+
+constexpr int kMaxP = FEDATTN_MAX_PARTICIPANTS;
+constexpr int kKvTile = 64;    // KV rows per MFMA prefill tile; also the keep-list tile
+constexpr int kWaveRows = 32;  // query rows per wave in the MFMA prefill kernel
+
+// Segment layout of the global sequence, passed by value in the kernel arguments
+// (read with scalar loads; no device copy of host arrays is needed).
+struct SegLayout {
+  int32_t n;                    // N participants
+  int32_t seg_off[kMaxP + 1];   // token offsets, seg_off[N] = total
+  int32_t tile_cum[kMaxP + 1];  // cumulative count of query tiles (tiles never straddle segments)
+  int32_t chunk_cum[kMaxP + 1]; // cumulative count of keep-list chunks
+};
+
+struct PrefillArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  int64_t q_block_stride;   // elements between consecutive blocks (batched launch)
+  int64_t kv_block_stride;
+  const uint8_t* keep_chunks;   // device, or nullptr
+  const int2* kept_tiles;       // device (workspace): (first token, valid rows) of kept 64-row tiles
+  const int32_t* kept_cum;      // device (workspace): kept tiles of participants < n, [N+1]
+  int32_t chunk_tokens;
+  int32_t total;
+  int32_t Hq, Hkv, D;
+  int32_t block_idx0;
+  int32_t sync_interval;
+  int32_t sync_override;    // -1 rule, 0 local, 1 sync
+  int32_t causal;
+  int32_t heads_per_wg;     // MFMA kernel: query heads of one KV group handled by one workgroup
+  int32_t q_tile_rows;      // MFMA kernel: query rows per workgroup
+  int32_t n_q_tiles;
+  float scale;              // softmax scale
+  SegLayout seg;
+};
+
+struct DecodeArgs {
+  const void* q;
+  const void* k_cache;
+  const void* v_cache;
+  void* out;
+  float* part_o;            // [Hkv, n_chunks, cols, D] fp32: sum_j p_j v_j with p_j = 2^(s_j - m), unnormalised
+  float* part_ml;           // [Hkv, n_chunks, cols, 2] (m in log2 domain, l)
+  int32_t N, Hq, Hkv, D;
+  int32_t is_sync;
+  int32_t chunk_rows;       // cache rows per workgroup
+  int32_t n_chunks;         // total chunks over all segments
+  int32_t cols;             // query columns per partial row block: G (local) or N*G (sync)
+  int32_t has_remote;       // remote_lens given
+  float scale;
+  int32_t seg_off[kMaxP + 1];
+  int32_t seg_lens[kMaxP];
+  int32_t remote_lens[kMaxP];
+  int32_t chunk_cum[kMaxP + 1];
+};
+
+struct AggregateArgs {
+  const void* k_local[kMaxP];
+  const void* v_local[kMaxP];
+  void* k_global;
+  void* v_global;
+  int32_t seg_off[kMaxP + 1];
+  int32_t n;
+  int32_t row_bytes;        // Hkv * D * element size, multiple of 16
+};
+
+// Host-side launchers (one per kernel family); each returns the hipError_t of the launch.
+hipError_t launch_prefill_generic(const PrefillArgs& a, int n_blocks, int dtype, hipStream_t s);
+hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s);
+hipError_t launch_build_kept_tiles(const PrefillArgs& a, int2* kept_tiles, int32_t* kept_cum,
+                                   hipStream_t s);
+hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t s);
+
+// Algorithm 1: block m = Ht + h (1-based) is the global-attention block iff h = H.
+__host__ __device__ inline bool sync_block_rule(int32_t H, int32_t block_idx) {
+  return H >= 1 && ((block_idx + 1) % H) == 0;
+}
+
+#if defined(__HIPCC__)
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even float -> bf16 (hardware conversion on gfx950)
+__device__ inline uint16_t f32_to_bf16_bits(float f) {
+  bf16_t b = (bf16_t)f;
+  return __builtin_bit_cast(uint16_t, b);
+}
+
+__device__ inline float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+#endif
+
+}  // namespace fedattn

@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle
+on the same seeded inputs.  Bar: max-abs 2e-2 and mean-abs 2e-3 for bf16 inputs,
+max-abs 1e-5 for fp32 inputs."""
+import numpy as np
+import pytest
+import torch
+
+import fedattn_inputs as fi
+import oracle
+import paper_2511_02647_amd as fa
+from gpu_util import check, decode, dev, host, prefill, say
+
+pytestmark = pytest.mark.gpu
+BF16, F32 = torch.bfloat16, torch.float32
+
+
+def rand_block(seed, total, Hq, Hkv, D, bf16=True, sigma=1.0):
+    g = np.random.default_rng(seed)
+    mk = lambda *s: (sigma * g.standard_normal(s)).astype(np.float32)
+    q, k, v = mk(total, Hq, D), mk(total, Hkv, D), mk(total, Hkv, D)
+    if bf16:
+        q, k, v = fi.round_to_bf16(q), fi.round_to_bf16(k), fi.round_to_bf16(v)
+    return q, k, v
+
+
+# ----------------------------------------------------------------- config 1
+def test_cfg1_tiny_fp32_all_blocks():
+    w = fi.workload("cfg1_tiny")
+    seg = w.seg_offsets
+    blocks = [fi.prefill_block(w, b) for b in range(w.n_blocks)]
+    ref = oracle.schedule.run_stack(*zip(*blocks), seg, w.sync_interval)
+    for b, (q, k, v) in enumerate(blocks):
+        say("cfg1 block %d" % b)
+        got = prefill(q, k, v, seg, Hq=2, Hkv=2, D=64, H=w.sync_interval, block=b, dtype=F32)
+        check(got, ref[b], F32, "cfg1_tiny fp32 block %d (%s)" % (b, "sync" if b % 2 else "local"))
+
+
+# ------------------------------------------------- general (ALU) kernel shapes
+@pytest.mark.parametrize("dtype,D,Hq,Hkv", [(F32, 64, 4, 2), (F32, 40, 3, 3), (BF16, 32, 4, 1), (F32, 256, 2, 1)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_general_kernel_shapes(dtype, D, Hq, Hkv, causal):
+    seg = np.array([0, 70, 70, 333, 391], dtype=np.int32)
+    q, k, v = rand_block(5, 391, Hq, Hkv, D, bf16=dtype == BF16)
+    for sync in (0, 1):
+        say("general kernel dtype=%s D=%d Hq=%d Hkv=%d causal=%d sync=%d" % (dtype, D, Hq, Hkv, causal, sync))
+        got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=dtype, causal=causal,
+                      sync_override=sync)
+        ref = oracle.attend_block(q, k, v, seg, is_sync=bool(sync), causal=causal)
+        check(got, ref, dtype, "general D=%d %s causal=%d sync=%d" % (D, dtype, causal, sync))
+
+
+def test_general_kernel_token_granular_keep_list():
+    seg = np.array([0, 50, 131, 200], dtype=np.int32)
+    q, k, v = rand_block(6, 200, 4, 2, 64, bf16=False)
+    flags = (np.random.default_rng(3).random(int(fi.chunk_counts(np.diff(seg), 8).sum())) < 0.5).astype(np.uint8)
+    kt = oracle.expand_keep_chunks(flags, seg, 8)
+    for causal in (True, False):
+        say("general kernel keep-list chunk=8 causal=%d" % causal)
+        got = prefill(q, k, v, seg, Hq=4, Hkv=2, D=64, H=1, block=0, dtype=F32, causal=causal,
+                      keep_chunks=flags, chunk_tokens=8)
+        ref = oracle.attend_block(q, k, v, seg, is_sync=True, causal=causal, keep_tok=kt)
+        check(got, ref, F32, "general keep-list chunk=8 causal=%d" % causal)
+
+
+# ------------------------------------------------------ MFMA kernel, small, full
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 2, 128), (2, 2, 128), (4, 2, 128), (8, 1, 128), (8, 2, 64), (3, 1, 64)])
+def test_mfma_prefill_small_full(Hq, Hkv, D):
+    seg = np.array([0, 100, 100, 137, 402, 403], dtype=np.int32)   # ragged, empty and 1-token segments
+    q, k, v = rand_block(7, 403, Hq, Hkv, D)
+    for causal in (True, False):
+        for sync in (0, 1):
+            say("mfma small Hq=%d Hkv=%d D=%d causal=%d sync=%d" % (Hq, Hkv, D, causal, sync))
+            got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, causal=causal,
+                          sync_override=sync)
+            ref = oracle.attend_block(q, k, v, seg, is_sync=bool(sync), causal=causal)
+            check(got, ref, BF16, "mfma Hq=%d Hkv=%d D=%d causal=%d sync=%d" % (Hq, Hkv, D, causal, sync))
+
+
+def test_mfma_prefill_sync_rule_and_scale():
+    seg = np.array([0, 96, 224], dtype=np.int32)
+    q, k, v = rand_block(8, 224, 4, 1, 128)
+    loc = oracle.attend_block(q, k, v, seg, is_sync=False, scale=0.05)
+    glo = oracle.attend_block(q, k, v, seg, is_sync=True, scale=0.05)
+    for H, b in [(2, 0), (2, 1), (3, 2), (3, 3), (0, 5), (1, 0)]:
+        say("sync rule H=%d block=%d" % (H, b))
+        got = prefill(q, k, v, seg, Hq=4, Hkv=1, D=128, H=H, block=b, dtype=BF16, scale=0.05)
+        sync = oracle.is_sync_block(H, b)
+        assert sync == fa.fedattn_is_sync_block(H, b)
+        check(got, glo if sync else loc, BF16, "rule H=%d block=%d -> %s" % (H, b, "sync" if sync else "local"))
+
+
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_mfma_prefill_sparse_exchange(chunk):
+    seg = np.array([0, 256, 256, 579, 900, 1001], dtype=np.int32)   # ragged last chunks
+    Hq, Hkv, D = 8, 2, 128
+    q, k, v = rand_block(9, 1001, Hq, Hkv, D)
+    nch = int(fi.chunk_counts(np.diff(seg), chunk).sum())
+    g = np.random.default_rng(4)
+    for name, flags in [("random", (g.random(nch) < 0.4).astype(np.uint8)),
+                        ("none", np.zeros(nch, np.uint8)), ("all", np.ones(nch, np.uint8))]:
+        kt = oracle.expand_keep_chunks(flags, seg, chunk)
+        for causal in (True, False):
+            say("mfma sparse chunk=%d keep=%s causal=%d" % (chunk, name, causal))
+            got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, causal=causal,
+                          keep_chunks=flags, chunk_tokens=chunk)
+            ref = oracle.attend_block(q, k, v, seg, is_sync=True, causal=causal, keep_tok=kt)
+            check(got, ref, BF16, "sparse chunk=%d keep=%s causal=%d" % (chunk, name, causal))
+    # a local block ignores the keep-list
+    flags = np.zeros(nch, np.uint8)
+    got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, keep_chunks=flags, chunk_tokens=chunk)
+    check(got, oracle.attend_block(q, k, v, seg, is_sync=False), BF16, "local block with keep-list")
+
+
+def test_prefill_blocks_batched_equals_per_block():
+    w = fi.workload("cfg2_llama8b_prefill")
+    seg = np.array([0, 130, 200, 333], dtype=np.int32)
+    M, H = 5, 2
+    blocks = [fi.prefill_block(w, b, total=333) for b in range(M)]
+    p = fa.make_params(3, w.n_q_heads, w.n_kv_heads, w.head_dim, H, BF16)
+    tq = torch.stack([dev(b[0], BF16) for b in blocks])
+    tk = torch.stack([dev(b[1], BF16) for b in blocks])
+    tv = torch.stack([dev(b[2], BF16) for b in blocks])
+    out = torch.full_like(tq, float("nan"))
+    say("prefill_blocks M=5 H=2")
+    fa.fedattn_prefill_blocks(p, 0, M, tq, tk, tv, out, tq[0].numel(), tk[0].numel(), seg)
+    torch.cuda.synchronize()
+    for b in range(M):
+        one = torch.full_like(tq[b], float("nan"))
+        fa.fedattn_prefill(p, b, tq[b], tk[b], tv[b], one, seg)
+        torch.cuda.synchronize()
+        assert torch.equal(one, out[b]), "batched launch differs from the per-block launch at block %d" % b
+        ref = oracle.attend_block(*blocks[b], seg, is_sync=oracle.is_sync_block(H, b))
+        check(host(out[b]), ref, BF16, "batched block %d" % b)
+
+
+# ------------------------------------------------------------- full-size configs
+def _sampled_check(q, k, v, seg, got, *, is_sync, n_random, what, keep_tok=None, salt=0):
+    rows, heads = fi.sample_rows(seg, q.shape[1], n_random, fi.DEFAULT_SEED, salt=salt)
+    ref = oracle.attend_rows(q, k, v, seg, rows, heads, is_sync=is_sync, keep_tok=keep_tok)
+    check(got[rows, heads], ref, BF16, what + " (%d sampled rows)" % len(rows))
+
+
+def test_cfg2_full_size():
+    w = fi.workload("cfg2_llama8b_prefill")
+    seg = w.seg_offsets
+    for b in (0, 3):
+        q, k, v = fi.prefill_block(w, b)
+        say("cfg2 block %d" % b)
+        got = prefill(q, k, v, seg, Hq=w.n_q_heads, Hkv=w.n_kv_heads, D=w.head_dim, H=w.sync_interval,
+                      block=b, dtype=BF16)
+        sync = oracle.is_sync_block(w.sync_interval, b)
+        assert sync == (b == 3)
+        _sampled_check(q, k, v, seg, got, is_sync=sync, n_random=3000, what="cfg2 block %d" % b, salt=b)
+
+
+def test_cfg3_full_size_sync_interval_sweep():
+    w = fi.workload("cfg3_hetero_prefill")
+    seg = w.seg_offsets
+    results = {}
+    for b in (0, 31):
+        q, k, v = fi.prefill_block(w, b)
+        tq, tk, tv = dev(q, BF16), dev(k, BF16), dev(v, BF16)
+        for H in (1, 4, 8, 32):
+            sync = oracle.is_sync_block(H, b)
+            say("cfg3 block %d H=%d (%s)" % (b, H, "sync" if sync else "local"))
+            p = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, H, BF16)
+            out = torch.full_like(tq, float("nan"))
+            fa.fedattn_prefill(p, b, tq, tk, tv, out, seg)
+            torch.cuda.synchronize()
+            if (b, sync) in results:     # same block, same kind of block: identical output
+                assert torch.equal(results[(b, sync)], out)
+                continue
+            results[(b, sync)] = out
+            _sampled_check(q, k, v, seg, host(out), is_sync=sync, n_random=2048,
+                           what="cfg3 block %d %s" % (b, "sync" if sync else "local"), salt=10 + b)
+        results.clear()
+        del tq, tk, tv
+
+
+def test_cfg5_sparse_sync_full_size():
+    w = fi.workload("cfg5_sparse_sync")
+    seg = w.seg_offsets
+    for b in (0, 1):
+        q, k, v = fi.prefill_block(w, b)
+        sync = oracle.is_sync_block(w.sync_interval, b)
+        flags = fi.keep_chunks(w, b // w.sync_interval)
+        kt = oracle.expand_keep_chunks(flags, seg, w.chunk_tokens)
+        say("cfg5 block %d (%s)" % (b, "sparse sync" if sync else "local"))
+        got = prefill(q, k, v, seg, Hq=w.n_q_heads, Hkv=w.n_kv_heads, D=w.head_dim, H=w.sync_interval,
+                      block=b, dtype=BF16, keep_chunks=flags, chunk_tokens=w.chunk_tokens)
+        _sampled_check(q, k, v, seg, got, is_sync=sync, n_random=1024, keep_tok=kt,
+                       what="cfg5 block %d" % b, salt=20 + b)
+
+
+# --------------------------------------------------------------------- decode
+@pytest.mark.parametrize("N,Hq,Hkv,D,dtype", [(3, 8, 2, 128, BF16), (1, 4, 1, 128, BF16), (20, 8, 2, 128, BF16),
+                                              (5, 6, 3, 64, BF16), (3, 4, 2, 64, F32), (2, 2, 1, 40, BF16)])
+def test_decode_small(N, Hq, Hkv, D, dtype):
+    cap = 300
+    g = np.random.default_rng(11)
+    seg = (np.arange(N + 1) * cap).astype(np.int32)
+    lens = g.integers(1, cap, size=N, endpoint=True).astype(np.int32)
+    lens[0] = cap
+    if N > 2:
+        lens[1] = 0          # a participant with an empty cache
+    prompt = np.minimum(lens, g.integers(0, cap, size=N)).astype(np.int32)
+    q, _, _ = rand_block(12, N, Hq, Hkv, D, bf16=dtype == BF16)
+    _, kc, vc = rand_block(13, N * cap, Hq, Hkv, D, bf16=dtype == BF16)
+    for sync, rl in [(0, None), (1, None), (1, prompt)]:
+        say("decode N=%d Hq=%d Hkv=%d D=%d %s sync=%d remote=%s" % (N, Hq, Hkv, D, dtype, sync, rl is not None))
+        got = decode(q, kc, vc, seg, lens, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=dtype,
+                     remote_lens=rl, sync_override=sync)
+        ref = oracle.decode_step(q, kc, vc, seg, lens, is_sync=bool(sync), remote_lens=rl)
+        check(got, ref, dtype, "decode N=%d D=%d sync=%d remote=%s" % (N, D, sync, rl is not None))
+
+
+def test_cfg4_decode_full_size():
+    w = fi.workload("cfg4_decode")
+    seg = w.seg_offsets
+    prompt = np.full(w.n_participants, 1024, dtype=np.int32)
+    for b in (0, 3):
+        kc, vc = fi.decode_cache_block(w, b)
+        for step in (0, 255):
+            lens = prompt + step + 1
+            q = fi.decode_query(w, step, b)
+            sync = oracle.is_sync_block(w.sync_interval, b)
+            readings = [None, prompt] if sync else [None]
+            for rl in readings:
+                say("cfg4 block %d step %d remote=%s" % (b, step, rl is not None))
+                got = decode(q, kc, vc, seg, lens, Hq=w.n_q_heads, Hkv=w.n_kv_heads, D=w.head_dim,
+                             H=w.sync_interval, block=b, dtype=BF16, remote_lens=rl)
+                ref = oracle.decode_step(q, kc, vc, seg, lens, is_sync=sync, remote_lens=rl)
+                check(got, ref, BF16, "cfg4 block %d step %d %s" % (b, step, "prompt-only remote" if rl is not None else "all cached"))
+
+
+# ------------------------------------------------------------------ aggregate
+@pytest.mark.parametrize("dtype", [BF16, F32])
+def test_aggregate_kv_bit_exact(dtype):
+    seg = np.array([0, 77, 77, 300, 1325], dtype=np.int32)
+    Hkv, D = 8, 128
+    _, k, v = rand_block(14, 1325, Hkv, Hkv, D, bf16=dtype == BF16)
+    kl = [k[seg[n]:seg[n + 1]] for n in range(4)]
+    vl = [v[seg[n]:seg[n + 1]] for n in range(4)]
+    Kref, Vref = oracle.aggregate_kv(kl, vl, seg)
+    p = fa.make_params(4, Hkv, Hkv, D, 1, dtype)
+    tkl = [dev(x, dtype) if x.shape[0] else None for x in kl]
+    tvl = [dev(x, dtype) if x.shape[0] else None for x in vl]
+    Kg = torch.full((1325, Hkv, D), float("nan"), dtype=dtype, device="cuda")
+    Vg = torch.full_like(Kg, float("nan"))
+    say("aggregate_kv %s" % dtype)
+    fa.fedattn_aggregate_kv(p, tkl, tvl, seg, Kg, Vg)
+    torch.cuda.synchronize()
+    assert np.array_equal(Kg.float().cpu().numpy(), Kref) and np.array_equal(Vg.float().cpu().numpy(), Vref)
+
+
+# --------------------------------------------------------------- error paths
+def test_errors_are_return_codes():
+    p = fa.make_params(2, 4, 2, 128, 1, BF16)
+    t = torch.zeros(64 * 4 * 128 + 8, dtype=BF16, device="cuda")
+    q = t[:64 * 4 * 128].view(64, 4, 128)
+    kv = torch.zeros(64, 2, 128, dtype=BF16, device="cuda")
+    out = torch.zeros_like(q)
+    with pytest.raises(fa.FedAttnError) as e:
+        fa.fedattn_prefill(p, 0, t[1:1 + 64 * 4 * 128].view(64, 4, 128), kv, kv, out, [0, 32, 64])
+    assert e.value.status == fa.FEDATTN_EINVAL
+    with pytest.raises(fa.FedAttnError) as e:
+        fa.fedattn_prefill(p, 0, q, kv, kv, out, [0, 40, 32])
+    assert e.value.status == fa.FEDATTN_EINVAL
+    flags = torch.ones(2, dtype=torch.uint8, device="cuda")
+    with pytest.raises(fa.FedAttnError) as e:
+        fa.fedattn_prefill(p, 0, q, kv, kv, out, [0, 32, 64], keep_chunks=flags, chunk_tokens=64)
+    assert e.value.status == fa.FEDATTN_EWORKSPACE
+    with pytest.raises(fa.FedAttnError) as e:
+        fa.fedattn_decode(p, 0, q[:2], kv, kv, out[:2], [0, 32, 64], [33, 1],
+                          workspace=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == fa.FEDATTN_EINVAL
+    with pytest.raises(fa.FedAttnError) as e:
+        fa.fedattn_decode(p, 0, q[:2], kv, kv, out[:2], [0, 32, 64], [32, 1])
+    assert e.value.status == fa.FEDATTN_EWORKSPACE
+    torch.cuda.synchronize()
