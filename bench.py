@@ -1,0 +1,350 @@
+#!/usr/bin/env python3
+"""Benchmark of the FedAttn attention hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: the
+attention of all M Transformer blocks of the workload, block after block (one
+launch per block, as the blocks of a model depend on each other), local blocks
+attending inside each participant's segment and every H-th block aggregating
+the participants' K/V (fedattn_aggregate_kv) and attending over the global KV.
+Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is useful attention TFLOP/s of the headline
+prefill workload (4*D*Hq*visible pairs; masked pairs and softmax not counted).
+`roofline` is for the dominant kernel (the MFMA prefill kernel), `decode`
+carries the split-KV decode kernel's achieved HBM GB/s on the decode workload,
+and `cpu_baseline` is the fp64 oracle timed on this machine's host cores on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import fedattn_inputs as fi  # noqa: E402
+import paper_2511_02647_amd as fa  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(msg: str) -> None:
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def to_dev_bf16(x: np.ndarray) -> torch.Tensor:
+    bits = fi.bf16_bits(x).view(np.int16)
+    return torch.from_numpy(bits).to("cuda").view(torch.bfloat16)
+
+
+def visible_pairs(seg: np.ndarray, is_sync: bool, keep_tok=None) -> int:
+    """Number of (query, key) pairs a causal block evaluates usefully (per head)."""
+    lens = np.diff(seg).astype(np.int64)
+    own = int((lens * (lens + 1) // 2).sum())
+    if not is_sync:
+        return own
+    if keep_tok is None:
+        L = int(seg[-1])
+        return L * (L + 1) // 2
+    kept_before = np.concatenate([[0], np.cumsum(keep_tok.astype(np.int64))])
+    remote = sum(int(lens[n]) * int(kept_before[seg[n]]) for n in range(len(lens)))
+    return own + remote
+
+
+def keep_tokens(flags: np.ndarray, seg: np.ndarray, chunk_tokens: int) -> np.ndarray:
+    """Per-token keep flags from per-chunk flags (for the useful-FLOP count only)."""
+    out = np.zeros(int(seg[-1]), dtype=np.uint8)
+    c = 0
+    for n in range(len(seg) - 1):
+        for t in range(int(seg[n]), int(seg[n + 1]), chunk_tokens):
+            out[t:min(t + chunk_tokens, int(seg[n + 1]))] = flags[c]
+            c += 1
+    return out
+
+
+class PrefillBench:
+    def __init__(self, name: str, n_data_blocks: int | None = None, H: int | None = None, aggregate: bool = True):
+        self.w = fi.workload(name)
+        w = self.w
+        self.H = w.sync_interval if H is None else H
+        self.seg = w.seg_offsets
+        self.M = w.n_blocks
+        self.aggregate = aggregate
+        nd = self.M if n_data_blocks is None else min(n_data_blocks, self.M)
+        self.nd = nd
+        t0 = time.time()
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            blocks = list(ex.map(lambda b: fi.prefill_block(w, b), range(nd)))
+        self.q = torch.stack([to_dev_bf16(b[0]) for b in blocks])
+        self.k = torch.stack([to_dev_bf16(b[1]) for b in blocks])
+        self.v = torch.stack([to_dev_bf16(b[2]) for b in blocks])
+        del blocks
+        self.out = torch.empty_like(self.q)
+        self.kg = torch.empty_like(self.k[0])
+        self.vg = torch.empty_like(self.v[0])
+        self.p = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, self.H, torch.bfloat16)
+        self.keep = None
+        self.ws = None
+        self.keep_tok = None
+        if w.chunk_tokens:
+            flags = [fi.keep_chunks(w, t) for t in range(max(1, self.M // max(self.H, 1)))]
+            self.keep = [torch.from_numpy(f).to("cuda") for f in flags]
+            self.keep_tok = [keep_tokens(f, self.seg, w.chunk_tokens) for f in flags]
+            nbytes = fa.fedattn_workspace_bytes(self.p, fa.FEDATTN_OP_PREFILL, w.total_tokens, w.chunk_tokens)
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.sync = [fa.fedattn_is_sync_block(self.H, b) for b in range(self.M)]
+        fl = 4 * w.head_dim * w.n_q_heads
+        self.flops_block = []
+        for b in range(self.M):
+            kt = None
+            if self.sync[b] and self.keep_tok is not None:
+                kt = self.keep_tok[(b // self.H) % len(self.keep_tok)]
+            self.flops_block.append(fl * visible_pairs(self.seg, self.sync[b], kt))
+        self.flops_step = float(sum(self.flops_block))
+        torch.cuda.synchronize()
+        log("%s: %d blocks (%d resident), H=%d, %d sync, %.1f GFLOP/step, inputs ready in %.1f s"
+            % (name, self.M, nd, self.H, sum(self.sync), self.flops_step / 1e9, time.time() - t0))
+
+    def local_views(self, d: int):
+        seg = self.seg
+        n = self.w.n_participants
+        return ([self.k[d][seg[i]:seg[i + 1]] for i in range(n)], [self.v[d][seg[i]:seg[i + 1]] for i in range(n)])
+
+    def run_block(self, b: int, ev=None):
+        d = b % self.nd
+        k, v = self.k[d], self.v[d]
+        kc = None
+        if self.sync[b]:
+            if self.aggregate:
+                kl, vl = self.local_views(d)
+                fa.fedattn_aggregate_kv(self.p, kl, vl, self.seg, self.kg, self.vg)
+                k, v = self.kg, self.vg
+            if self.keep is not None:
+                kc = self.keep[(b // self.H) % len(self.keep)]
+        if ev is not None:
+            ev[0].record()
+        fa.fedattn_prefill(self.p, b, self.q[d], k, v, self.out[d], self.seg, keep_chunks=kc,
+                           chunk_tokens=self.w.chunk_tokens, workspace=self.ws)
+        if ev is not None:
+            ev[1].record()
+
+    def step(self):
+        for b in range(self.M):
+            self.run_block(b)
+
+    def kernel_times(self, steps: int):
+        """Average duration of the prefill kernel per block kind, HIP events around each launch."""
+        evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                for _ in range(self.M)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        for s in range(steps):
+            for b in range(self.M):
+                self.run_block(b, evs[s][b])
+        torch.cuda.synchronize()
+        ms = np.array([[e[0].elapsed_time(e[1]) for e in row] for row in evs])  # [steps, M]
+        return ms
+
+
+class DecodeBench:
+    def __init__(self, name: str = "cfg4_decode", n_data_blocks: int | None = None):
+        self.w = fi.workload(name)
+        w = self.w
+        self.M = w.n_blocks
+        self.seg = w.seg_offsets
+        nd = self.M if n_data_blocks is None else min(n_data_blocks, self.M)
+        self.nd = nd
+        t0 = time.time()
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            caches = list(ex.map(lambda b: fi.decode_cache_block(w, b), range(nd)))
+        self.kc = torch.stack([to_dev_bf16(c[0]) for c in caches])
+        self.vc = torch.stack([to_dev_bf16(c[1]) for c in caches])
+        del caches
+        nq = 8
+        self.q = torch.stack([to_dev_bf16(fi.decode_query(w, s, 0)) for s in range(nq)])
+        self.out = torch.empty_like(self.q[0])
+        self.p = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, w.sync_interval,
+                                torch.bfloat16)
+        nbytes = fa.fedattn_workspace_bytes(self.p, fa.FEDATTN_OP_DECODE, w.total_tokens)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.prompt = 1024
+        self.sync = [fa.fedattn_is_sync_block(w.sync_interval, b) for b in range(self.M)]
+        torch.cuda.synchronize()
+        log("%s: %d blocks (%d resident caches), inputs ready in %.1f s" % (name, self.M, nd, time.time() - t0))
+
+    def bytes_block_step(self, step: int) -> float:
+        w = self.w
+        rows = w.n_participants * (self.prompt + step + 1)
+        return float(rows * w.n_kv_heads * w.head_dim * 2 * 2)
+
+    def run_step(self, step: int, ev=None):
+        lens = np.full(self.w.n_participants, self.prompt + step + 1, dtype=np.int32)
+        for b in range(self.M):
+            d = b % self.nd
+            if ev is not None:
+                ev[b][0].record()
+            fa.fedattn_decode(self.p, b, self.q[(step + b) % self.q.shape[0]], self.kc[d], self.vc[d], self.out,
+                              self.seg, lens, workspace=self.ws)
+            if ev is not None:
+                ev[b][1].record()
+
+
+def time_region(fn, steps: int, warmup: int) -> float:
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(pb: PrefillBench, budget_s: float = 15.0) -> dict:
+    """The oracle, as it stands, on a bounded sample of the headline workload."""
+    import oracle
+    w = pb.w
+    q, k, v = fi.prefill_block(w, 3)
+    seg = pb.seg
+    sync = oracle.is_sync_block(pb.H, 3)
+    rows, heads = fi.sample_rows(seg, w.n_q_heads, 256, fi.DEFAULT_SEED, salt=77)
+    rows, heads = rows[-256:], heads[-256:]
+
+    def pairs(rs):
+        owner = np.searchsorted(seg, rs, side="right") - 1
+        return int(np.sum(rs + 1 - (0 if sync else seg[owner])))
+
+    t0 = time.perf_counter()
+    oracle.attend_rows(q, k, v, seg, rows, heads, is_sync=sync)
+    dt = time.perf_counter() - t0
+    rate = pairs(rows) / dt
+    n_more = int(min(200000, max(256, budget_s * rate / max(1.0, pairs(rows) / len(rows)))))
+    rows2, heads2 = fi.sample_rows(seg, w.n_q_heads, n_more, fi.DEFAULT_SEED, salt=78)
+    rows2, heads2 = rows2[-n_more:], heads2[-n_more:]
+    t0 = time.perf_counter()
+    oracle.attend_rows(q, k, v, seg, rows2, heads2, is_sync=sync)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * w.head_dim * pairs(rows2)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.n_threads(), "kind": "oracle",
+            "sample": "%d random (row, head) pairs of block 3 (%s) of %s, fp64, %.1f s"
+                      % (len(rows2), "sync" if sync else "local", w.name, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2_llama8b_prefill",
+                    choices=["cfg2_llama8b_prefill", "cfg3_hetero_prefill", "cfg5_sparse_sync"])
+    ap.add_argument("--sync-interval", type=int, default=None, help="override H of the workload")
+    ap.add_argument("--no-aggregate", action="store_true", help="skip fedattn_aggregate_kv in sync blocks")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode measurement")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=8, help="decode steps timed (spread over the 256)")
+    ap.add_argument("--data-blocks", type=int, default=None, help="distinct input blocks kept resident")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (participants are segments of one batch); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    fa.load()
+
+    nd = args.data_blocks
+    if nd is None and args.workload != "cfg2_llama8b_prefill":
+        nd = 4   # 336 MB (cfg3) / 0.8 GB (cfg5) of inputs per block: keep a few distinct ones
+    pb = PrefillBench(args.workload, nd, args.sync_interval, aggregate=not args.no_aggregate)
+    sec = time_region(pb.step, args.steps, args.warmup)
+    tflops = pb.flops_step / sec / 1e12
+    log("%s: %.3f ms/step, %.1f useful TFLOP/s" % (pb.w.name, sec * 1e3, tflops))
+
+    # dominant kernel: HIP events around every prefill launch, same steps again
+    ms = pb.kernel_times(min(args.steps, 10))
+    kern_ms = ms.sum(axis=1).mean()
+    achieved = pb.flops_step / (kern_ms * 1e-3) / 1e12
+    sync_idx = [b for b in range(pb.M) if pb.sync[b]]
+    loc_idx = [b for b in range(pb.M) if not pb.sync[b]]
+    roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+            "kernel": "prefill_mfma_kernel<128>", "launches_per_step": pb.M,
+            "avg_launch_us": float(ms.mean() * 1e3),
+            "avg_local_us": float(ms[:, loc_idx].mean() * 1e3) if loc_idx else None,
+            "avg_sync_us": float(ms[:, sync_idx].mean() * 1e3) if sync_idx else None,
+            "local_tflops": (np.mean([pb.flops_block[b] for b in loc_idx]) / (ms[:, loc_idx].mean() * 1e-3) / 1e12)
+            if loc_idx else None,
+            "sync_tflops": (np.mean([pb.flops_block[b] for b in sync_idx]) / (ms[:, sync_idx].mean() * 1e-3) / 1e12)
+            if sync_idx else None}
+    log("prefill kernel: avg %.1f us/launch -> %.1f TFLOP/s (%.1f%% of bf16 MFMA peak)"
+        % (roof["avg_launch_us"], achieved, 100 * roof["frac"]))
+
+    result = {"metric": "prefill attn TFLOP/s (% bf16 MFMA peak); decode HBM GB/s (% peak)",
+              "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+              "dtype": "bf16", "data": "synthetic",
+              "config": {"workload": pb.w.name, "participants": pb.w.n_participants,
+                         "seg_lens": [int(x) for x in pb.w.seg_lens], "blocks": pb.M, "sync_interval": pb.H,
+                         "q_heads": pb.w.n_q_heads, "kv_heads": pb.w.n_kv_heads, "head_dim": pb.w.head_dim,
+                         "launch": "one fedattn_prefill per block, fedattn_aggregate_kv before each sync block"
+                                   if pb.aggregate else "one fedattn_prefill per block"},
+              "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS,
+              "roofline": roof}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(pb)
+        log("cpu oracle: %.5f TFLOP/s on %d threads" % (result["cpu_baseline"]["value"], result["cpu_baseline"]["cores"]))
+    del pb
+    torch.cuda.empty_cache()
+
+    if not args.no_decode:
+        db = DecodeBench()
+        steps = sorted(set(int(s) for s in np.linspace(0, db.w.decode_steps - 1, args.decode_steps)))
+        for s in steps[:2]:
+            db.run_step(s)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in steps:
+            db.run_step(s)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        total_bytes = sum(db.bytes_block_step(s) * db.M for s in steps)
+        # kernel-level: events around each block-step (split + combine kernels)
+        evs = {s: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                   for _ in range(db.M)] for s in steps}
+        for s in steps:
+            db.run_step(s, evs[s])
+        torch.cuda.synchronize()
+        ms = np.array([[e[0].elapsed_time(e[1]) for e in evs[s]] for s in steps])
+        byts = np.array([[db.bytes_block_step(s)] * db.M for s in steps])
+        sync_mask = np.array(db.sync)
+        gbs = lambda m: float(byts[:, m].sum() / (ms[:, m].sum() * 1e-3) / 1e9)
+        dec = {"workload": db.w.name, "steps_timed": steps, "blocks": db.M,
+               "end_to_end_GBps": total_bytes / wall / 1e9,
+               "ms_per_decode_step": wall / len(steps) * 1e3,
+               "roofline": {"bound": "hbm", "achieved": gbs(slice(None)), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": gbs(slice(None)) / PEAK_HBM_GBS, "traffic": None,
+                            "kernel": "decode_split_kernel + decode_combine_kernel",
+                            "local_GBps": gbs(~sync_mask), "sync_GBps": gbs(sync_mask),
+                            "avg_local_us": float(ms[:, ~sync_mask].mean() * 1e3),
+                            "avg_sync_us": float(ms[:, sync_mask].mean() * 1e3)}}
+        result["decode"] = dec
+        log("decode: %.0f GB/s by events (local %.0f, sync %.0f), %.0f GB/s end to end"
+            % (dec["roofline"]["achieved"], dec["roofline"]["local_GBps"], dec["roofline"]["sync_GBps"],
+               dec["end_to_end_GBps"]))
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
