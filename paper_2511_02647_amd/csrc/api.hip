@@ -137,14 +137,17 @@ fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t 
   const int G = a.Hq / a.Hkv;
   a.heads_per_wg = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
   a.q_tile_rows = kWaveRows * (4 / a.heads_per_wg);
-  int64_t tiles = 0, chunks = 0;
+  int64_t tiles = 0, chunks = 0, pairs = 0;
   for (int n = 0; n <= N; ++n) {
     a.seg.seg_off[n] = seg[n];
     a.seg.tile_cum[n] = (int32_t)tiles;
     a.seg.chunk_cum[n] = (int32_t)chunks;
+    a.seg.pair_cum[n] = (int32_t)pairs;
     if (n < N) {
       const int64_t len = seg[n + 1] - seg[n];
-      tiles += (len + a.q_tile_rows - 1) / a.q_tile_rows;
+      const int64_t tn = (len + a.q_tile_rows - 1) / a.q_tile_rows;
+      tiles += tn;
+      pairs += (tn + 1) / 2;
       if (has_keep) chunks += (len + chunk_tokens - 1) / chunk_tokens;
     }
   }

@@ -20,6 +20,7 @@ struct SegLayout {
   int32_t seg_off[kMaxP + 1];   // token offsets, seg_off[N] = total
   int32_t tile_cum[kMaxP + 1];  // cumulative count of query tiles (tiles never straddle segments)
   int32_t chunk_cum[kMaxP + 1]; // cumulative count of keep-list chunks
+  int32_t pair_cum[kMaxP + 1];  // cumulative count of query-tile pairs, tiles paired inside each segment
 };
 
 struct PrefillArgs {
