@@ -78,6 +78,30 @@ __device__ inline uint32_t lds_addr_of(const void* p) {
   return (uint32_t)(uintptr_t)(lds_void_ptr)p;
 }
 
+// Both halves of a wavefront's 32-lane rows: returns (value of lane%32, value of
+// lane%32 + 32) in every lane (v_permlane32_swap: no LDS round trip).
+__device__ inline void both_halves(float x, float& lo, float& hi) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];
+  lo = __uint_as_float(a);
+  hi = __uint_as_float(b);
+}
+__device__ inline float max_across_halves(float x) {
+  float lo, hi;
+  both_halves(x, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ inline float sum_across_halves(float x) {
+  float lo, hi;
+  both_halves(x, lo, hi);
+  return lo + hi;
+}
+
+// scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier
+#define SGB_MFMA 0x008
+#define SGB_DS_READ 0x100
+
 // Waits until this wavefront's direct-to-LDS loads have landed (vmcnt(0) only).
 __device__ inline void wait_lds_dma() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
@@ -281,34 +305,59 @@ __global__ __launch_bounds__(256, FEDATTN_PREFILL_OCC) void prefill_mfma_kernel(
     auto compute_s = [&](int kb, f32x16 (&s)[2]) __attribute__((always_inline)) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[0][e] = 0.f; s[1][e] = 0.f; }
+      bf16x8 kf[KSTEPS][2];
 #pragma unroll
       for (int st = 0; st < KSTEPS; ++st) {
         const lds_cptr ptr = lds0 + (k_off[st] + kb);
 #pragma unroll
-        for (int aa = 0; aa < 2; ++aa) {
-          const bf16x8 kf = __builtin_bit_cast(
+        for (int aa = 0; aa < 2; ++aa)
+          kf[st][aa] = __builtin_bit_cast(
               bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(ptr + 32 * aa * ROWB));
-          s[aa] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[aa], 0, 0, 0);
-        }
       }
+#pragma unroll
+      for (int st = 0; st < KSTEPS; ++st)
+#pragma unroll
+        for (int aa = 0; aa < 2; ++aa) s[aa] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st][aa], qf[st], s[aa], 0, 0, 0);
+      // keep the LDS reads kLookS k-steps ahead of the MFMAs that consume them
+      constexpr int kLookS = 3;
+      __builtin_amdgcn_sched_group_barrier(SGB_DS_READ, 2 * kLookS, 0);
+#pragma unroll
+      for (int st = 0; st < KSTEPS - kLookS; ++st) {
+        __builtin_amdgcn_sched_group_barrier(SGB_MFMA, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(SGB_DS_READ, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(SGB_MFMA, 2 * kLookS, 0);
     };
     // O^T[d][q] += V^T P^T from the V stage at LDS byte offset vb; k-step kk covers tile
     // rows 16 kk + {4hf..4hf+3, 8+4hf..8+4hf+3}, the order in which P^T sits in the
-    // lane's registers.
+    // lane's registers.  k-step major, so that the first MFMAs need only the first
+    // quarter of P.
     auto compute_pv = [&](int vb, const bf16x8 (&pb)[4]) __attribute__((always_inline)) {
+      bf16x8 vf[4][DT];
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const lds_cptr base = lds0 + (v_off[dt] + vb);
+      for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const lds_cptr ptr = base + 16 * kk * ROWB;
+        for (int dt = 0; dt < DT; ++dt) {
+          const lds_cptr ptr = lds0 + (v_off[dt] + vb) + 16 * kk * ROWB;
           const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)ptr);
           const s16x4 hi =
               __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(ptr + 8 * ROWB));
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kk], o[dt], 0, 0, 0);
+          vf[kk][dt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][dt], pb[kk], o[dt], 0, 0, 0);
+      constexpr int kLookV = 4;        // MFMAs of lookahead
+      constexpr int NM = 4 * DT;       // MFMAs in this product
+      __builtin_amdgcn_sched_group_barrier(SGB_DS_READ, 2 * kLookV, 0);
+#pragma unroll
+      for (int i = 0; i < NM - kLookV; ++i) {
+        __builtin_amdgcn_sched_group_barrier(SGB_MFMA, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(SGB_DS_READ, 2, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(SGB_MFMA, kLookV, 0);
     };
 
     // ---- prologue: K and V tile 0 into stage 0 -----------------------------------------
@@ -363,7 +412,7 @@ __global__ __launch_bounds__(256, FEDATTN_PREFILL_OCC) void prefill_mfma_kernel(
         mx1 = fmaxf(fmaxf(mx1, s_cur[0][e + 1]), s_cur[1][e + 1]);
       }
       float mx = fmaxf(mx0, mx1);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = max_across_halves(mx);
       const float m_cand = mx * sc;
 
       // the accumulators follow the row maximum lazily: rescale only when some row's
@@ -402,7 +451,7 @@ __global__ __launch_bounds__(256, FEDATTN_PREFILL_OCC) void prefill_mfma_kernel(
     }
 
     // ---- normalise and write ---------------------------------------------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (my_row < seg_hi) {
       uint16_t* orow = op + ((int64_t)my_row * Hq + head) * D + 4 * hf;
