@@ -16,7 +16,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfedattn.so")
+LIB_PATH = os.environ.get("FEDATTN_LIB") or os.path.join(_HERE, "libfedattn.so")
 
 FEDATTN_OK, FEDATTN_EINVAL, FEDATTN_EUNSUPPORTED, FEDATTN_EWORKSPACE, FEDATTN_ELAUNCH = range(5)
 FEDATTN_BF16, FEDATTN_F32 = 0, 1
