@@ -67,11 +67,34 @@ int env_int(const char* name, int dflt) {
   return v > 0 ? v : dflt;
 }
 
-// cache rows per decode workgroup (multiples of 128: 4 wavefronts x 32 rows)
-int decode_chunk_rows(bool sync) {
-  static const int local_rows = (env_int("FEDATTN_DECODE_CHUNK_LOCAL", 256) + 127) / 128 * 128;
-  static const int sync_rows = (env_int("FEDATTN_DECODE_CHUNK_SYNC", 512) + 127) / 128 * 128;
-  return sync ? sync_rows : local_rows;
+// Decode splits every participant's cache segment into chunks of `rows` cache rows (a
+// multiple of the 64-row tile), one workgroup per (chunk, KV head).  The split aims at
+// one workgroup per CU: about n_cus / Hkv chunks over all segments.
+int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+int decode_target_chunks(int Hkv) {
+  const int t = device_cus() / Hkv;
+  return t < 1 ? 1 : t;
+}
+
+int decode_chunk_rows(int64_t total_rows, int Hkv) {
+  static const int forced = env_int("FEDATTN_DECODE_CHUNK", 0);
+  if (forced > 0) return (forced + kKvTile - 1) / kKvTile * kKvTile;
+  const int64_t target = decode_target_chunks(Hkv);
+  int64_t rows = (total_rows + target - 1) / target;
+  rows = (rows + kKvTile - 1) / kKvTile * kKvTile;
+  return (int)(rows < kKvTile ? kKvTile : rows);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -87,11 +110,10 @@ size_t decode_ws_bytes(const fedattn_params* p, int32_t capacity) {
   if (!(p->dtype == FEDATTN_BF16 && (p->head_dim == 64 || p->head_dim == 128))) return 16;
   const size_t G = (size_t)(p->n_q_heads / p->n_kv_heads);
   const size_t N = (size_t)p->n_participants;
-  const size_t ch_local = (size_t)capacity / decode_chunk_rows(false) + N;
-  const size_t ch_sync = (size_t)capacity / decode_chunk_rows(true) + N;
-  const size_t rows_local = (size_t)p->n_kv_heads * ch_local * G;
-  const size_t rows_sync = (size_t)p->n_kv_heads * ch_sync * G * N;
-  const size_t rows = rows_local > rows_sync ? rows_local : rows_sync;
+  // chunks <= sum_n (rows_n / chunk_rows + 1) <= target + N (or capacity/forced + N)
+  static const int forced = env_int("FEDATTN_DECODE_CHUNK", 0);
+  const size_t chunks = (forced > 0 ? (size_t)capacity / (size_t)forced + 1 : (size_t)decode_target_chunks(p->n_kv_heads)) + N;
+  const size_t rows = (size_t)p->n_kv_heads * chunks * G * N;  // sync blocks: N*G query columns per chunk
   return align_up(rows * (size_t)p->head_dim * 4, 256) + align_up(rows * 8, 256);
 }
 
@@ -251,7 +273,12 @@ fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, c
   a.scale = resolve_scale(params);
   const int G = a.Hq / a.Hkv;
   a.cols = sync ? N * G : G;
-  a.chunk_rows = decode_chunk_rows(sync);
+  int64_t total_rows = 0;
+  for (int n = 0; n < N; ++n) {
+    const int rem = (sync && remote_lens) ? remote_lens[n] : seg_lens[n];
+    total_rows += sync ? (seg_lens[n] > rem ? seg_lens[n] : rem) : seg_lens[n];
+  }
+  a.chunk_rows = decode_chunk_rows(total_rows, a.Hkv);
   int64_t chunks = 0;
   for (int n = 0; n <= N; ++n) {
     a.seg_off[n] = seg_offsets[n];

@@ -4,49 +4,48 @@
 // Split-KV: a workgroup takes one chunk of one participant's cache segment for
 // one KV head and ALL query rows that may see it - the G query heads of that
 // participant in a local block, the N*G rows of all participants in a sync block
-// (the aggregated cache is read once for everybody).  Each of the 4 wavefronts
-// streams its own 32-row sub-tiles straight from HBM into MFMA operand registers
-// (K) or through a private LDS transpose (V), keeps an online softmax per query
-// column, and the wavefronts are merged at the end.  A second small kernel merges
-// the chunks: o = sum_c O_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
-//
-// Products run transposed on the 16x16x32 bf16 MFMA: S^T[kv][q] = K Q^T and
-// O^T[d][q] += V^T P^T, so a query column lives in 4 lanes (lane%16) and P^T feeds
-// the second product from registers.
+// (the aggregated cache is read once for everybody).  The chunk streams through a
+// 4-stage LDS ring of 64-row K/V tiles filled by direct HBM -> LDS loads, three
+// tiles in flight per workgroup, one workgroup per CU.  The query rows form one or
+// two 32-row MFMA tiles; the wavefronts that share a query tile take the KV tiles
+// round-robin, each with its own online softmax, and are merged at the end.  A
+// second small kernel merges the chunks:
+//   o = sum_c O_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 #include "common.h"
+#include "mfma_tile.h"
 
 namespace fedattn {
 
 namespace {
 
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kSubRows = 32;  // cache rows per wavefront step
+constexpr int kDecodeStages = 4;
 
-__device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xFFFFu) | (b << 16); }
-__device__ inline uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xFFFF0000u); }
+template <int D>
+constexpr int decode_smem_bytes() { return kDecodeStages * 2 * KvTile<D>::TILEB; }
 
-template <int D, int NQT>
-__global__ __launch_bounds__(256, (NQT <= 2 ? 2 : 1)) void decode_split_kernel(DecodeArgs a) {
-  constexpr int KS = D / 32;          // MFMA k-steps of S^T
-  constexpr int DT = D / 16;          // 16-row tiles of O^T along head_dim
-  constexpr int VP = D / 64;          // V load passes (a wave covers 64 head_dim columns per pass)
-  constexpr int QCOLS = 16 * NQT;     // query columns per workgroup
-  constexpr int RSQ = D * 2 + 16;     // LDS bytes per Q row
-  constexpr int RSV = kSubRows * 2 + 16;  // LDS bytes per V^T row (one wave's 32 cache rows)
-  constexpr int OPAD = D + 4;         // floats per row of the merge buffer
-  constexpr int VT_BYTES = 4 * D * RSV;
-  constexpr int OS_BYTES = QCOLS * OPAD * 4;
-  constexpr int SCR_BYTES = VT_BYTES > OS_BYTES ? VT_BYTES : OS_BYTES;
-  __shared__ __attribute__((aligned(16))) unsigned char q_lds[QCOLS * RSQ];
-  __shared__ __attribute__((aligned(16))) unsigned char scr[SCR_BYTES];  // V^T per wave, later the merge buffer
-  __shared__ float m_s[4][QCOLS];
-  __shared__ float l_s[4][QCOLS];
+template <int D, int NQS>
+__global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
+  using TL = KvTile<D>;
+  constexpr int KSTEPS = TL::KSTEPS, DT = TL::DT, TILEB = TL::TILEB, IPW = TL::IPW;
+  constexpr int KP = 4 / NQS;        // wavefronts sharing one query tile, KV tiles round-robin
+  constexpr int QCOLS = 32 * NQS;    // query columns per workgroup
+  constexpr int OPAD = D + 4;        // floats per row of the merge buffer
+  static_assert(QCOLS * OPAD * 4 <= kDecodeStages * 2 * TILEB, "merge buffer must fit in the tile ring");
+  // stage s: K tile at s*2*TILEB, V tile at s*2*TILEB + TILEB; after the stream the
+  // ring is reused as the merge buffer
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  __shared__ float m_s[4][32];
+  __shared__ float l_s[4][32];
+  const lds_cptr lds0 = (lds_cptr)(lds_void_ptr)smem;
+  const uint32_t lds_base = lds_addr_of(smem);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int l16 = lane & 15;
-  const int kg = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31;
+  const int hf = lane >> 5;
+  const int qs = wave % NQS;   // query tile of this wavefront
+  const int kp = wave / NQS;   // its turn among the KV tiles
 
   const int Hq = a.Hq, Hkv = a.Hkv;
   const int G = Hq / Hkv;
@@ -64,199 +63,106 @@ __global__ __launch_bounds__(256, (NQT <= 2 ? 2 : 1)) void decode_split_kernel(D
   const int min_limit = sync ? min(own_len, rem_len) : own_len;
   const int r_lo = c * a.chunk_rows;
   const int r_hi = min(r_lo + a.chunk_rows, rows_end);
+  const int nt = (r_hi - r_lo + kKvTile - 1) / kKvTile;
+  const int row_elems = Hkv * D;
 
-  const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q);
-  const uint16_t* kp = reinterpret_cast<const uint16_t*>(a.k_cache) + ((int64_t)a.seg_off[m] * Hkv + g) * D;
-  const uint16_t* vp = reinterpret_cast<const uint16_t*>(a.v_cache) + ((int64_t)a.seg_off[m] * Hkv + g) * D;
-  const int64_t row_stride = (int64_t)Hkv * D;
+  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(a.k_cache) + ((int64_t)(a.seg_off[m] + r_lo) * Hkv + g) * D;
+  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(a.v_cache) + ((int64_t)(a.seg_off[m] + r_lo) * Hkv + g) * D;
 
-  // query column -> (participant, head); columns past the end read zeros
-  auto col_participant = [&](int col) { return sync ? col / G : m; };
-  auto col_head = [&](int col) { return g * G + (sync ? col % G : col); };
+  TL tile_io;
+  tile_io.init(lane, wave, row_elems);
 
-  // stage Q into LDS
-  for (int idx = tid; idx < QCOLS * (D / 8); idx += 256) {
-    const int cl = idx / (D / 8), ch = idx % (D / 8);
-    const int col = cb + cl;
-    uint4 w = make_uint4(0, 0, 0, 0);
-    if (col < a.cols)
-      w = *reinterpret_cast<const uint4*>(qp + ((int64_t)col_participant(col) * Hq + col_head(col)) * D + ch * 8);
-    *reinterpret_cast<uint4*>(q_lds + cl * RSQ + ch * 16) = w;
-  }
-  __syncthreads();
-
-  // rows of this segment visible to the query column in lane l16 of column tile qt
-  int limit[NQT];
+  // this lane's query column -> (participant, head); columns past the end are zero
+  // rows: local block, column = head inside the KV group; sync block, column =
+  // participant * G + head inside the group.  The loads are written out (like the tile
+  // loads) so that the compiler's own wait for them does not drain the tile ring; they
+  // are the oldest loads of the wavefront, so the first tile wait covers them.
+  const int col = cb + 32 * qs + l32;
+  const bool col_ok = col < a.cols;
+  const int col_part = sync ? col / G : m;
+  const int col_head = g * G + (sync ? col % G : col);
+  const int limit = col_ok ? (col_part == m ? own_len : rem_len) : 0;  // visible rows of this segment
+  u32x4 qw[KSTEPS];
+  {
+    const uint16_t* qrow = reinterpret_cast<const uint16_t*>(a.q) +
+                           ((int64_t)(col_ok ? col_part : 0) * Hq + (col_ok ? col_head : 0)) * D + 8 * hf;
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const int col = cb + 16 * qt + l16;
-    limit[qt] = col >= a.cols ? 0 : (col_participant(col) == m ? own_len : rem_len);
+    for (int st = 0; st < KSTEPS; ++st)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qw[st]) : "v"(qrow + 16 * st) : "memory");
   }
 
-  f32x4 o[DT][NQT];
+  auto issue = [&](int t) __attribute__((always_inline)) {
+    const int len = min(kKvTile, r_hi - r_lo - kKvTile * t);
+    const uint32_t stage = lds_base + (t % kDecodeStages) * 2 * TILEB;
+    tile_io.template dma<false>(kbase + (int64_t)t * kKvTile * row_elems, stage, len);
+    tile_io.template dma<true>(vbase + (int64_t)t * kKvTile * row_elems, stage + TILEB, len);
+  };
+#pragma unroll
+  for (int t = 0; t < kDecodeStages - 1; ++t)
+    if (t < nt) issue(t);
+
+  f32x16 o[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) o[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run[NQT], l_run[NQT];
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
+    for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
   const float sc = a.scale * kLog2e;
 
-  unsigned char* vt = scr + wave * (D * RSV);
-  const int v_rg = lane & 7;   // group of 4 cache rows this lane transposes
-  const int v_dc = lane >> 3;  // 8-wide head_dim chunk (plus 8 per pass)
-  const int v_pos = (((v_rg & 3) << 1) | (v_rg >> 2)) * 8;  // groups kg and 4+kg end up adjacent
+  for (int t = 0; t < nt; ++t) {
+    // this wavefront's part of tile t has landed once at most the loads of the tiles
+    // issued after it are outstanding
+    const int after = min(nt, t + kDecodeStages - 1) - (t + 1);
+    if (after >= 2)
+      wait_vmcnt<2 * 2 * IPW>();
+    else if (after == 1)
+      wait_vmcnt<2 * IPW>();
+    else
+      wait_vmcnt<0>();
+    __syncthreads();  // tile t is complete in LDS, and everyone is done with tile t-1
+#pragma unroll
+    for (int st = 0; st < KSTEPS; ++st) asm volatile("" : "+v"(qw[st]));  // the query loads have landed by now
+    if (t + kDecodeStages - 1 < nt) issue(t + kDecodeStages - 1);  // into the stage tile t-1 used
 
-  uint4 kreg[2][KS];
-  uint4 vreg[VP][4];
-  auto load_sub = [&](int r0) {
+    if (t % KP == kp) {
+      const int kb = (t % kDecodeStages) * 2 * TILEB;
+      bf16x8 qf[KSTEPS];
 #pragma unroll
-    for (int aa = 0; aa < 2; ++aa) {
-      const int row = min(r0 + 16 * aa + l16, r_hi - 1);
-#pragma unroll
-      for (int st = 0; st < KS; ++st)
-        kreg[aa][st] = *reinterpret_cast<const uint4*>(kp + row * row_stride + 32 * st + 8 * kg);
-    }
-#pragma unroll
-    for (int ps = 0; ps < VP; ++ps)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int row = min(r0 + 4 * v_rg + r, r_hi - 1);
-        vreg[ps][r] = *reinterpret_cast<const uint4*>(vp + row * row_stride + 8 * (v_dc + 8 * ps));
+      for (int st = 0; st < KSTEPS; ++st) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        qf[st] = __builtin_bit_cast(bf16x8, col_ok ? qw[st] : zero);
       }
-  };
-
-  int r0 = r_lo + kSubRows * wave;
-  if (r0 < r_hi) load_sub(r0);
-
-  for (; r0 < r_hi; r0 += 4 * kSubRows) {
-    // take this sub-tile out of the prefetch registers
-    bf16x8 kf[2][KS];
-#pragma unroll
-    for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-      for (int st = 0; st < KS; ++st) kf[aa][st] = __builtin_bit_cast(bf16x8, kreg[aa][st]);
-#pragma unroll
-    for (int ps = 0; ps < VP; ++ps) {
-      const uint32_t w0[4] = {vreg[ps][0].x, vreg[ps][0].y, vreg[ps][0].z, vreg[ps][0].w};
-      const uint32_t w1[4] = {vreg[ps][1].x, vreg[ps][1].y, vreg[ps][1].z, vreg[ps][1].w};
-      const uint32_t w2[4] = {vreg[ps][2].x, vreg[ps][2].y, vreg[ps][2].z, vreg[ps][2].w};
-      const uint32_t w3[4] = {vreg[ps][3].x, vreg[ps][3].y, vreg[ps][3].z, vreg[ps][3].w};
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int d = 8 * (v_dc + 8 * ps) + 2 * p;
-        uint2 ev, od;
-        ev.x = pack_lo(w0[p], w1[p]);
-        ev.y = pack_lo(w2[p], w3[p]);
-        od.x = pack_hi(w0[p], w1[p]);
-        od.y = pack_hi(w2[p], w3[p]);
-        *reinterpret_cast<uint2*>(vt + d * RSV + v_pos) = ev;
-        *reinterpret_cast<uint2*>(vt + (d + 1) * RSV + v_pos) = od;
-      }
+      f32x16 s[2];
+      tile_io.scores(lds0, kb, qf, s);
+      const int row0 = r_lo + kKvTile * t;
+      if (row0 + kKvTile > min_limit) mask_scores(s, limit - row0, hf);
+      bf16x8 pb[4];
+      softmax_step<DT>(s, sc, m_run, l_run, o, pb);
+      tile_io.pv(lds0, kb + TILEB, pb, o);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-
-    const int r_next = r0 + 4 * kSubRows;
-    if (r_next < r_hi) load_sub(r_next);  // in flight during the MFMAs below
-
-    // ---- S^T[kv][q] = K Q^T ---------------------------------------------------
-    f32x4 s[2][NQT];
-#pragma unroll
-    for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) s[aa][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-      for (int st = 0; st < KS; ++st) {
-        const bf16x8 qf = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const uint4*>(q_lds + (16 * qt + l16) * RSQ + (32 * st + 8 * kg) * 2));
-        s[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][st], qf, s[0][qt], 0, 0, 0);
-        s[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][st], qf, s[1][qt], 0, 0, 0);
-      }
-    // element e of s[aa][qt]: cache row r0 + 16*aa + 4*kg + e, query column 16*qt + l16
-
-    if (r0 + kSubRows > min_limit) {
-#pragma unroll
-      for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (r0 + 16 * aa + 4 * kg + e >= limit[qt]) s[aa][qt][e] = -INFINITY;
-    }
-
-    // ---- online softmax per query column ----------------------------------------
-    bf16x8 pb[NQT];
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, s[aa][qt][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[qt], mx * sc);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_use);
-      m_run[qt] = m_new;
-      float psum = 0.f;
-#pragma unroll
-      for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[aa][qt][e], sc, -m_use));
-          psum += p;
-          pb[qt][4 * aa + e] = (bf16_t)p;
-        }
-      l_run[qt] = l_run[qt] * alpha + psum;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[dt][qt] *= alpha;
-    }
-
-    // ---- O^T[d][q] += V^T P^T -------------------------------------------------------
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      const bf16x8 vf = __builtin_bit_cast(
-          bf16x8, *reinterpret_cast<const uint4*>(vt + (16 * dt + l16) * RSV + kg * 16));
-#pragma unroll
-      for (int qt = 0; qt < NQT; ++qt)
-        o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[qt], o[dt][qt], 0, 0, 0);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
   }
 
-  // ---- merge the 4 wavefronts -------------------------------------------------------
+  // ---- merge the wavefronts that share a query tile ------------------------------------
+  const float l_full = sum_across_halves(l_run);
+  if (hf == 0) m_s[wave][l32] = m_run;
+  __syncthreads();  // also: every wavefront is done with the tile ring
+  float mm = -INFINITY;
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    l_run[qt] += __shfl_xor(l_run[qt], 16, 64);
-    l_run[qt] += __shfl_xor(l_run[qt], 32, 64);
-    if (kg == 0) m_s[wave][16 * qt + l16] = m_run[qt];
-  }
-  __syncthreads();  // also: every wave is done with its V^T region
-  float f[NQT];
+  for (int k2 = 0; k2 < KP; ++k2) mm = fmaxf(mm, m_s[k2 * NQS + qs][l32]);
+  const float mu = (mm == -INFINITY) ? 0.f : mm;
+  const float f = __builtin_amdgcn_exp2f(m_run - mu);
+  if (hf == 0) l_s[wave][l32] = l_full * f;
+  float* o_s = reinterpret_cast<float*>(smem);
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const int cl = 16 * qt + l16;
-    const float mm = fmaxf(fmaxf(m_s[0][cl], m_s[1][cl]), fmaxf(m_s[2][cl], m_s[3][cl]));
-    const float mu = (mm == -INFINITY) ? 0.f : mm;
-    f[qt] = __builtin_amdgcn_exp2f(m_run[qt] - mu);
-    if (kg == 0) l_s[wave][cl] = l_run[qt] * f[qt];
-  }
-  float* o_s = reinterpret_cast<float*>(scr);
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
+  for (int k2 = 0; k2 < KP; ++k2) {
+    if (kp == k2) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-          float* dst = o_s + (16 * qt + l16) * OPAD + 16 * dt + 4 * kg;
-          f32x4 val = o[dt][qt] * f[qt];
-          if (w > 0) val += *reinterpret_cast<const f32x4*>(dst);
+        for (int vq = 0; vq < 4; ++vq) {
+          float* dst = o_s + (32 * qs + l32) * OPAD + 32 * dt + 8 * vq + 4 * hf;
+          f32x4 val = {o[dt][4 * vq] * f, o[dt][4 * vq + 1] * f, o[dt][4 * vq + 2] * f, o[dt][4 * vq + 3] * f};
+          if (k2 > 0) val += *reinterpret_cast<const f32x4*>(dst);
           *reinterpret_cast<f32x4*>(dst) = val;
         }
     }
@@ -271,16 +177,23 @@ __global__ __launch_bounds__(256, (NQT <= 2 ? 2 : 1)) void decode_split_kernel(D
         *reinterpret_cast<const f32x4*>(o_s + cl * OPAD + 4 * d4);
   }
   if (tid < n_cols) {
-    const float mm = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
-    const float ll = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
-    a.part_ml[(prow0 + tid) * 2] = mm;
-    a.part_ml[(prow0 + tid) * 2 + 1] = ll;
+    const int q2 = tid >> 5, c32 = tid & 31;
+    float m2 = -INFINITY, l2 = 0.f;
+#pragma unroll
+    for (int k2 = 0; k2 < KP; ++k2) {
+      m2 = fmaxf(m2, m_s[k2 * NQS + q2][c32]);
+      l2 += l_s[k2 * NQS + q2][c32];
+    }
+    a.part_ml[(prow0 + tid) * 2] = m2;
+    a.part_ml[(prow0 + tid) * 2 + 1] = l2;
   }
 }
 
 // Merges the chunk partials of one (participant, query head) and writes the output row.
 template <typename T>
-__global__ void decode_combine_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
+  __shared__ float w_s[256];
+  __shared__ float red_s[8];
   const int n = blockIdx.x / a.Hq;
   const int h = blockIdx.x % a.Hq;
   const int G = a.Hq / a.Hkv;
@@ -289,20 +202,44 @@ __global__ void decode_combine_kernel(DecodeArgs a) {
   const int c1 = a.is_sync ? a.n_chunks : a.chunk_cum[n + 1];
   const int col = a.is_sync ? n * G + hh : hh;
   const int64_t base = (int64_t)g * a.n_chunks;
+  const int tid = threadIdx.x;
+  const int D = a.D;
 
+  // row maximum over the chunks
   float mm = -INFINITY;
-  for (int cc = c0; cc < c1; ++cc) mm = fmaxf(mm, a.part_ml[((base + cc) * a.cols + col) * 2]);
+  for (int cc = c0 + tid; cc < c1; cc += blockDim.x) mm = fmaxf(mm, a.part_ml[((base + cc) * a.cols + col) * 2]);
+  mm = wave_max(mm);
+  if ((tid & 63) == 0) red_s[tid >> 6] = mm;
+  __syncthreads();
+  mm = -INFINITY;
+  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) mm = fmaxf(mm, red_s[w]);
   const float mu = (mm == -INFINITY) ? 0.f : mm;
-  for (int d = threadIdx.x; d < a.D; d += blockDim.x) {
-    float num = 0.f, den = 0.f;
-    for (int cc = c0; cc < c1; ++cc) {
-      const int64_t prow = (base + cc) * a.cols + col;
-      const float fc = __builtin_amdgcn_exp2f(a.part_ml[prow * 2] - mu);
-      den = fmaf(a.part_ml[prow * 2 + 1], fc, den);
-      num = fmaf(a.part_o[prow * a.D + d], fc, num);
+
+  float acc = 0.f, den = 0.f;
+  for (int cb = c0; cb < c1; cb += 256) {
+    const int nb = min(256, c1 - cb);
+    __syncthreads();
+    for (int i = tid; i < nb; i += blockDim.x)
+      w_s[i] = __builtin_amdgcn_exp2f(a.part_ml[((base + cb + i) * a.cols + col) * 2] - mu);
+    __syncthreads();
+    if (tid < D) {
+      int i = 0;
+      for (; i + 4 <= nb; i += 4) {
+        const float* p0 = a.part_o + ((base + cb + i) * a.cols + col) * D + tid;
+        const int64_t st = (int64_t)a.cols * D;
+        const float x0 = p0[0], x1 = p0[st], x2 = p0[2 * st], x3 = p0[3 * st];
+        acc = fmaf(x0, w_s[i], acc);
+        acc = fmaf(x1, w_s[i + 1], acc);
+        acc = fmaf(x2, w_s[i + 2], acc);
+        acc = fmaf(x3, w_s[i + 3], acc);
+      }
+      for (; i < nb; ++i) acc = fmaf(a.part_o[((base + cb + i) * a.cols + col) * D + tid], w_s[i], acc);
     }
-    const float val = den > 0.f ? num / den : 0.f;
-    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * a.D + d;
+    for (int i = 0; i < nb; ++i) den = fmaf(a.part_ml[((base + cb + i) * a.cols + col) * 2 + 1], w_s[i], den);
+  }
+  if (tid < D) {
+    const float val = den > 0.f ? acc / den : 0.f;
+    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * D + tid;
     if constexpr (sizeof(T) == 2)
       *out = f32_to_bf16_bits(val);
     else
@@ -387,15 +324,23 @@ __global__ __launch_bounds__(64) void decode_rows_kernel(DecodeArgs a) {
 }
 
 template <int D>
-hipError_t launch_split(const DecodeArgs& a, hipStream_t s) {
-  const int qcols = a.cols <= 16 ? 16 : (a.cols <= 32 ? 32 : 64);
+hipError_t launch_stream(const DecodeArgs& a, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes<D>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes<D>());
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int qcols = a.cols <= 32 ? 32 : 64;
   dim3 grid((unsigned)(a.n_chunks * a.Hkv), (unsigned)((a.cols + qcols - 1) / qcols), 1);
-  if (qcols == 16)
-    hipLaunchKernelGGL((decode_split_kernel<D, 1>), grid, dim3(256), 0, s, a);
-  else if (qcols == 32)
-    hipLaunchKernelGGL((decode_split_kernel<D, 2>), grid, dim3(256), 0, s, a);
+  if (qcols == 32)
+    hipLaunchKernelGGL((decode_stream_kernel<D, 1>), grid, dim3(256), decode_smem_bytes<D>(), s, a);
   else
-    hipLaunchKernelGGL((decode_split_kernel<D, 4>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((decode_stream_kernel<D, 2>), grid, dim3(256), decode_smem_bytes<D>(), s, a);
   return hipGetLastError();
 }
 
@@ -413,11 +358,11 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
     return hipGetLastError();
   }
   if (a.n_chunks > 0) {
-    hipError_t e = a.D == 128 ? launch_split<128>(a, s) : launch_split<64>(a, s);
+    hipError_t e = a.D == 128 ? launch_stream<128>(a, s) : launch_stream<64>(a, s);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq)),
-                     dim3((unsigned)a.D), 0, s, a);
+  hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq)), dim3(a.D <= 64 ? 64 : 128), 0,
+                     s, a);
   return hipGetLastError();
 }
 
