@@ -145,6 +145,22 @@ fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, c
                               size_t workspace_bytes, void* stream);
 
 /*
+ * The same for n_blocks consecutive blocks block_idx0 .. block_idx0+n_blocks-1 of one
+ * decoding step in one host call: block b reads q + b*q_block_stride and the caches
+ * + b*cache_block_stride (strides in elements, multiples of 8) and writes
+ * out + b*q_block_stride; all blocks share the segment layout and lengths.  The
+ * blocks are enqueued one after the other (each with its own launches, as the blocks
+ * of a model depend on each other); results equal n_blocks calls of fedattn_decode.
+ * The workspace is reused from block to block in stream order.
+ */
+fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                     const void* q, const void* k_cache, const void* v_cache, void* out,
+                                     int64_t q_block_stride, int64_t cache_block_stride,
+                                     const int32_t* seg_offsets, const int32_t* seg_lens,
+                                     const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
+/*
  * KV aggregation of a sync block (Phase II): [K V] = sum_n Pi_n [k_n v_n], i.e.
  * row r of participant n's local k_n, v_n lands at global row seg_offsets[n] + r.
  *   k_local,v_local host arrays of N device pointers, entry n -> [len_n,Hkv,D]

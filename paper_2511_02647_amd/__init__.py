@@ -24,7 +24,7 @@ FEDATTN_OP_PREFILL, FEDATTN_OP_DECODE = 0, 1
 FEDATTN_MAX_PARTICIPANTS = 128
 
 EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill",
-           "fedattn_prefill_blocks", "fedattn_decode", "fedattn_aggregate_kv",
+           "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_aggregate_kv",
            "fedattn_last_error", "fedattn_version")
 
 
@@ -65,6 +65,8 @@ def load():
     lib.fedattn_prefill_blocks.restype = ctypes.c_int
     lib.fedattn_decode.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.fedattn_decode.restype = ctypes.c_int
+    lib.fedattn_decode_blocks.argtypes = [pp, i32, i32, vp, vp, vp, vp, i64, i64, vp, vp, vp, i32, vp, sz, vp]
+    lib.fedattn_decode_blocks.restype = ctypes.c_int
     lib.fedattn_aggregate_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.fedattn_aggregate_kv.restype = ctypes.c_int
     lib.fedattn_last_error.restype = ctypes.c_char_p
@@ -169,6 +171,29 @@ def fedattn_decode(params: fedattn_params, block_idx: int, q: torch.Tensor, k_ca
                                  seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
                                  None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
                                  int(sync_override), _dev(workspace, "workspace"), ws_bytes, _stream(stream)))
+
+
+def fedattn_decode_blocks(params: fedattn_params, block_idx0: int, n_blocks: int, q: torch.Tensor,
+                          k_cache: torch.Tensor, v_cache: torch.Tensor, out: torch.Tensor, q_block_stride: int,
+                          cache_block_stride: int, seg_offsets, seg_lens, remote_lens=None, sync_override: int = -1,
+                          workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    lens = _host_i32(seg_lens, "seg_lens")
+    if seg.shape[0] != params.n_participants + 1 or lens.shape[0] != params.n_participants:
+        raise ValueError("seg_offsets / seg_lens have the wrong length")
+    rl = None
+    if remote_lens is not None:
+        rl = _host_i32(remote_lens, "remote_lens")
+        if rl.shape[0] != params.n_participants:
+            raise ValueError("remote_lens has the wrong length")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().fedattn_decode_blocks(ctypes.byref(params), int(block_idx0), int(n_blocks), _dev(q, "q"),
+                                        _dev(k_cache, "k_cache"), _dev(v_cache, "v_cache"), _dev(out, "out"),
+                                        int(q_block_stride), int(cache_block_stride),
+                                        seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
+                                        None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
+                                        int(sync_override), _dev(workspace, "workspace"), ws_bytes,
+                                        _stream(stream)))
 
 
 def fedattn_aggregate_kv(params: fedattn_params, k_local: Sequence[Optional[torch.Tensor]],

@@ -238,16 +238,18 @@ fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t bloc
                      nullptr, 0, -1, nullptr, 0, stream);
 }
 
-fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q, const void* k_cache,
-                              const void* v_cache, void* out, const int32_t* seg_offsets, const int32_t* seg_lens,
-                              const int32_t* remote_lens, int32_t sync_override, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                     const void* q, const void* k_cache, const void* v_cache, void* out,
+                                     int64_t q_block_stride, int64_t cache_block_stride,
+                                     const int32_t* seg_offsets, const int32_t* seg_lens,
+                                     const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
   fedattn_status st = check_params(params);
   if (st != FEDATTN_OK) return st;
   st = check_offsets(params, seg_offsets);
   if (st != FEDATTN_OK) return st;
   if (!seg_lens) return fail(FEDATTN_EINVAL, "seg_lens is NULL");
-  if (block_idx < 0) return fail(FEDATTN_EINVAL, "negative block index");
+  if (block_idx0 < 0 || n_blocks < 0) return fail(FEDATTN_EINVAL, "negative block index or count");
   if (sync_override < -1 || sync_override > 1) return fail(FEDATTN_EINVAL, "sync_override must be -1, 0 or 1");
   const int N = params->n_participants;
   for (int n = 0; n < N; ++n) {
@@ -257,58 +259,81 @@ fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, c
     if (remote_lens && (remote_lens[n] < 0 || remote_lens[n] > cap))
       return fail(FEDATTN_EINVAL, "remote_lens[%d] = %d outside 0..capacity %d", n, remote_lens[n], cap);
   }
+  if (n_blocks == 0) return FEDATTN_OK;
   if (!q || !out) return fail(FEDATTN_EINVAL, "q and out must not be NULL");
   const int32_t capacity = seg_offsets[N];
   if (capacity > 0 && (!k_cache || !v_cache)) return fail(FEDATTN_EINVAL, "k_cache and v_cache must not be NULL");
   if (!aligned16(q) || !aligned16(out) || !aligned16(k_cache) || !aligned16(v_cache))
     return fail(FEDATTN_EINVAL, "q, out, k_cache and v_cache must be 16-byte aligned");
+  if (n_blocks > 1 && (q_block_stride % 8 != 0 || cache_block_stride % 8 != 0 || q_block_stride < 0 ||
+                       cache_block_stride < 0))
+    return fail(FEDATTN_EINVAL, "block strides must be non-negative multiples of 8 elements");
 
-  DecodeArgs a;
-  memset(&a, 0, sizeof(a));
-  a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.out = out;
-  a.N = N; a.Hq = params->n_q_heads; a.Hkv = params->n_kv_heads; a.D = params->head_dim;
-  const bool sync = sync_override >= 0 ? sync_override != 0 : sync_block_rule(params->sync_interval, block_idx);
-  a.is_sync = sync ? 1 : 0;
-  a.has_remote = (sync && remote_lens) ? 1 : 0;
-  a.scale = resolve_scale(params);
-  const int G = a.Hq / a.Hkv;
-  a.cols = sync ? N * G : G;
-  int64_t total_rows = 0;
-  for (int n = 0; n < N; ++n) {
-    const int rem = (sync && remote_lens) ? remote_lens[n] : seg_lens[n];
-    total_rows += sync ? (seg_lens[n] > rem ? seg_lens[n] : rem) : seg_lens[n];
-  }
-  a.chunk_rows = decode_chunk_rows(total_rows, a.Hkv);
-  int64_t chunks = 0;
-  for (int n = 0; n <= N; ++n) {
-    a.seg_off[n] = seg_offsets[n];
-    a.chunk_cum[n] = (int32_t)chunks;
-    if (n < N) {
-      a.seg_lens[n] = seg_lens[n];
-      a.remote_lens[n] = remote_lens ? remote_lens[n] : seg_lens[n];
-      const int rem = a.has_remote ? a.remote_lens[n] : seg_lens[n];
-      const int rows = sync ? (seg_lens[n] > rem ? seg_lens[n] : rem) : seg_lens[n];
-      chunks += (rows + a.chunk_rows - 1) / a.chunk_rows;
+  const bool mfma = params->dtype == FEDATTN_BF16 && (params->head_dim == 64 || params->head_dim == 128);
+  const size_t esize = params->dtype == FEDATTN_BF16 ? 2 : 4;
+  DecodeArgs args[2];  // [0] local block, [1] sync block: the split differs, the layout does not
+  bool built[2] = {false, false};
+  for (int b = 0; b < n_blocks; ++b) {
+    const bool sync =
+        sync_override >= 0 ? sync_override != 0 : sync_block_rule(params->sync_interval, block_idx0 + b);
+    DecodeArgs& a = args[sync ? 1 : 0];
+    if (!built[sync ? 1 : 0]) {
+      memset(&a, 0, sizeof(a));
+      a.N = N; a.Hq = params->n_q_heads; a.Hkv = params->n_kv_heads; a.D = params->head_dim;
+      a.is_sync = sync ? 1 : 0;
+      a.has_remote = (sync && remote_lens) ? 1 : 0;
+      a.scale = resolve_scale(params);
+      const int G = a.Hq / a.Hkv;
+      a.cols = sync ? N * G : G;
+      int64_t total_rows = 0;
+      for (int n = 0; n < N; ++n) {
+        const int rem = a.has_remote ? remote_lens[n] : seg_lens[n];
+        total_rows += sync ? (seg_lens[n] > rem ? seg_lens[n] : rem) : seg_lens[n];
+      }
+      a.chunk_rows = decode_chunk_rows(total_rows, a.Hkv);
+      int64_t chunks = 0;
+      for (int n = 0; n <= N; ++n) {
+        a.seg_off[n] = seg_offsets[n];
+        a.chunk_cum[n] = (int32_t)chunks;
+        if (n < N) {
+          a.seg_lens[n] = seg_lens[n];
+          a.remote_lens[n] = remote_lens ? remote_lens[n] : seg_lens[n];
+          const int rem = a.has_remote ? a.remote_lens[n] : seg_lens[n];
+          const int rows = sync ? (seg_lens[n] > rem ? seg_lens[n] : rem) : seg_lens[n];
+          chunks += (rows + a.chunk_rows - 1) / a.chunk_rows;
+        }
+      }
+      a.n_chunks = (int32_t)chunks;
+      if (mfma) {
+        const size_t need = decode_ws_bytes(params, capacity);
+        if (!workspace || workspace_bytes < need)
+          return fail(FEDATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need, workspace_bytes);
+        if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
+        const size_t rows = (size_t)a.Hkv * (size_t)a.n_chunks * (size_t)a.cols;
+        const size_t o_bytes = align_up(rows * (size_t)a.D * 4, 256);
+        if (o_bytes + rows * 8 > workspace_bytes)
+          return fail(FEDATTN_EWORKSPACE, "decode partials (%zu bytes) exceed the workspace", o_bytes + rows * 8);
+        a.part_o = reinterpret_cast<float*>(workspace);
+        a.part_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + o_bytes);
+      }
+      built[sync ? 1 : 0] = true;
     }
+    a.q = reinterpret_cast<const unsigned char*>(q) + (size_t)b * (size_t)q_block_stride * esize;
+    a.out = reinterpret_cast<unsigned char*>(out) + (size_t)b * (size_t)q_block_stride * esize;
+    a.k_cache = reinterpret_cast<const unsigned char*>(k_cache) + (size_t)b * (size_t)cache_block_stride * esize;
+    a.v_cache = reinterpret_cast<const unsigned char*>(v_cache) + (size_t)b * (size_t)cache_block_stride * esize;
+    hipError_t e = launch_decode(a, params->dtype, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (block %d): %s", block_idx0 + b, hipGetErrorString(e));
   }
-  a.n_chunks = (int32_t)chunks;
-
-  const bool mfma = params->dtype == FEDATTN_BF16 && (a.D == 64 || a.D == 128);
-  if (mfma) {
-    const size_t need = decode_ws_bytes(params, capacity);
-    if (!workspace || workspace_bytes < need)
-      return fail(FEDATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need, workspace_bytes);
-    if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
-    const size_t rows = (size_t)a.Hkv * (size_t)a.n_chunks * (size_t)a.cols;
-    const size_t o_bytes = align_up(rows * (size_t)a.D * 4, 256);
-    if (o_bytes + rows * 8 > workspace_bytes)
-      return fail(FEDATTN_EWORKSPACE, "decode partials (%zu bytes) exceed the workspace", o_bytes + rows * 8);
-    a.part_o = reinterpret_cast<float*>(workspace);
-    a.part_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + o_bytes);
-  }
-  hipError_t e = launch_decode(a, params->dtype, reinterpret_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode: %s", hipGetErrorString(e));
   return FEDATTN_OK;
+}
+
+fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, const int32_t* seg_offsets, const int32_t* seg_lens,
+                              const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  return fedattn_decode_blocks(params, block_idx, 1, q, k_cache, v_cache, out, 0, 0, seg_offsets, seg_lens,
+                               remote_lens, sync_override, workspace, workspace_bytes, stream);
 }
 
 fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* const* k_local,

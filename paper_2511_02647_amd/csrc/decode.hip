@@ -5,11 +5,14 @@
 // one KV head and ALL query rows that may see it - the G query heads of that
 // participant in a local block, the N*G rows of all participants in a sync block
 // (the aggregated cache is read once for everybody).  The chunk streams through a
-// 4-stage LDS ring of 64-row K/V tiles filled by direct HBM -> LDS loads, three
-// tiles in flight per workgroup, one workgroup per CU.  The query rows form one or
-// two 32-row MFMA tiles; the wavefronts that share a query tile take the KV tiles
-// round-robin, each with its own online softmax, and are merged at the end.  A
-// second small kernel merges the chunks:
+// 4-stage LDS ring of 64-row K/V tiles filled by direct HBM -> LDS loads (three
+// tiles in flight per workgroup, one workgroup per CU).  Every wavefront works on
+// every tile: wavefront w takes tile rows 16w..16w+15 against all query columns,
+// S^T[kv][q] = K Q^T on v_mfma_f32_16x16x32_bf16 and O^T[d][q] += V^T P^T on
+// v_mfma_f32_16x16x16_bf16, whose k-slots are exactly the 4 rows per lane that the
+// first product leaves in a lane, with V^T operands from transposing LDS reads.  Each
+// wavefront keeps its own online softmax per query column; the wavefronts are merged
+// at the end and a second small kernel merges the chunks:
 //   o = sum_c O_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
 #include "common.h"
 #include "mfma_tile.h"
@@ -23,35 +26,53 @@ constexpr int kDecodeStages = 4;
 template <int D>
 constexpr int decode_smem_bytes() { return kDecodeStages * 2 * KvTile<D>::TILEB; }
 
-template <int D, int NQS>
+// value of x maximised / summed over the 4 lanes (lane%16 + 16 k) that share a query column
+__device__ inline float max_over_kgroups(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];
+  return max_across_halves(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+}
+__device__ inline float sum_over_kgroups(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];
+  return sum_across_halves(__uint_as_float(a) + __uint_as_float(b));
+}
+
+// COLSPLIT = false (at most 16 query columns, e.g. the G heads of one participant in a
+// local block): wavefront w takes tile rows 16w..16w+15; the 4 wavefronts are merged
+// through LDS at the end.  COLSPLIT = true (up to 64 query columns, sync blocks):
+// wavefront w takes query columns 16w..16w+15 against all 64 tile rows, so every
+// wavefront owns its output columns and nothing has to be merged.
+template <int D, bool COLSPLIT>
 __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   using TL = KvTile<D>;
-  constexpr int KSTEPS = TL::KSTEPS, DT = TL::DT, TILEB = TL::TILEB, IPW = TL::IPW;
-  constexpr int KP = 4 / NQS;        // wavefronts sharing one query tile, KV tiles round-robin
-  constexpr int QCOLS = 32 * NQS;    // query columns per workgroup
-  constexpr int OPAD = D + 4;        // floats per row of the merge buffer
-  static_assert(QCOLS * OPAD * 4 <= kDecodeStages * 2 * TILEB, "merge buffer must fit in the tile ring");
+  constexpr int KS = D / 32;                 // k-steps of S^T (16x16x32)
+  constexpr int DT = D / 16;                 // 16-row tiles of O^T along head_dim
+  constexpr int CPR = TL::CPR, ROWB = TL::ROWB, TILEB = TL::TILEB, IPW = TL::IPW;
+  constexpr int RSUB = COLSPLIT ? 4 : 1;     // 16-row sub-tiles a wavefront processes per tile
+  constexpr int QCOLS = COLSPLIT ? 64 : 16;  // query columns per workgroup
+  constexpr int OPAD = D + 4;                // floats per row of the merge buffer
   // stage s: K tile at s*2*TILEB, V tile at s*2*TILEB + TILEB; after the stream the
-  // ring is reused as the merge buffer
+  // ring is reused as the merge buffer (row split only)
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  __shared__ float m_s[4][32];
-  __shared__ float l_s[4][32];
+  __shared__ float m_s[4][16];
+  __shared__ float l_s[4][16];
   const lds_cptr lds0 = (lds_cptr)(lds_void_ptr)smem;
   const uint32_t lds_base = lds_addr_of(smem);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31;
-  const int hf = lane >> 5;
-  const int qs = wave % NQS;   // query tile of this wavefront
-  const int kp = wave / NQS;   // its turn among the KV tiles
+  const int l16 = lane & 15;
+  const int kg = lane >> 4;
 
   const int Hq = a.Hq, Hkv = a.Hkv;
   const int G = Hq / Hkv;
   const int g = blockIdx.x % Hkv;
   const int gc = blockIdx.x / Hkv;  // chunk index over all segments
-  const int cb = blockIdx.y * QCOLS;
+  const int cb = blockIdx.y * QCOLS + (COLSPLIT ? 16 * wave : 0);  // first query column of this wavefront
 
   int m = 0;
   while (gc >= a.chunk_cum[m + 1]) ++m;
@@ -76,19 +97,19 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   // rows: local block, column = head inside the KV group; sync block, column =
   // participant * G + head inside the group.  The loads are written out (like the tile
   // loads) so that the compiler's own wait for them does not drain the tile ring; they
-  // are the oldest loads of the wavefront, so the first tile wait covers them.
-  const int col = cb + 32 * qs + l32;
+  // are issued before any tile load, so the first tile wait below covers them.
+  const int col = cb + l16;
   const bool col_ok = col < a.cols;
-  const int col_part = sync ? col / G : m;
-  const int col_head = g * G + (sync ? col % G : col);
+  const bool wave_has_cols = cb < a.cols;  // wave-uniform
+  const int col_part = col_ok ? (sync ? col / G : m) : 0;
+  const int col_head = col_ok ? g * G + (sync ? col % G : col) : 0;
   const int limit = col_ok ? (col_part == m ? own_len : rem_len) : 0;  // visible rows of this segment
-  u32x4 qw[KSTEPS];
+  u32x4 qw[KS];  // B operand of S^T: Q[col][32 st + 8 kg .. +8]
   {
-    const uint16_t* qrow = reinterpret_cast<const uint16_t*>(a.q) +
-                           ((int64_t)(col_ok ? col_part : 0) * Hq + (col_ok ? col_head : 0)) * D + 8 * hf;
+    const uint16_t* qrow = reinterpret_cast<const uint16_t*>(a.q) + ((int64_t)col_part * Hq + col_head) * D + 8 * kg;
 #pragma unroll
-    for (int st = 0; st < KSTEPS; ++st)
-      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qw[st]) : "v"(qrow + 16 * st) : "memory");
+    for (int st = 0; st < KS; ++st)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qw[st]) : "v"(qrow + 32 * st) : "memory");
   }
 
   auto issue = [&](int t) __attribute__((always_inline)) {
@@ -101,17 +122,32 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   for (int t = 0; t < kDecodeStages - 1; ++t)
     if (t < nt) issue(t);
 
-  f32x16 o[DT];
+  // LDS -> A operand of S^T: lane (row l16 of a 16-row sub-tile, k-group kg) reads chunk
+  // 4 st + kg; the sub-tile's first row goes in the address as a multiple of 16 rows,
+  // which leaves the swizzle term unchanged
+  int k_off[KS];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int st = 0; st < KS; ++st) k_off[st] = l16 * ROWB + (((4 * st + kg) ^ (l16 & (CPR - 1))) * 16);
+  // LDS -> A operand of O^T: transposing 8-byte reads; lane i = 4 e + c of a 16-lane group
+  // supplies the address of V[sub-tile row 4 kg + e][16 dt + 4 c ..] and receives
+  // V[sub-tile rows 4 kg + 0..3][16 dt + i]
+  int v_off[DT];
+  {
+    const int vrow = 4 * kg + (l16 >> 2);
+    const int fv = (2 * (vrow & 7)) & (CPR - 1);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+    for (int dt = 0; dt < DT; ++dt) v_off[dt] = vrow * ROWB + (((2 * dt + ((l16 & 3) >> 1)) ^ fv) * 16) + (l16 & 1) * 8;
+  }
+
+  f32x4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = a.scale * kLog2e;
 
   for (int t = 0; t < nt; ++t) {
     // this wavefront's part of tile t has landed once at most the loads of the tiles
-    // issued after it are outstanding
+    // issued after it are outstanding (the query loads are older still)
     const int after = min(nt, t + kDecodeStages - 1) - (t + 1);
     if (after >= 2)
       wait_vmcnt<2 * 2 * IPW>();
@@ -121,71 +157,113 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
       wait_vmcnt<0>();
     __syncthreads();  // tile t is complete in LDS, and everyone is done with tile t-1
 #pragma unroll
-    for (int st = 0; st < KSTEPS; ++st) asm volatile("" : "+v"(qw[st]));  // the query loads have landed by now
+    for (int st = 0; st < KS; ++st) asm volatile("" : "+v"(qw[st]));  // the query loads have landed by now
     if (t + kDecodeStages - 1 < nt) issue(t + kDecodeStages - 1);  // into the stage tile t-1 used
+    if (COLSPLIT && !wave_has_cols) continue;
 
-    if (t % KP == kp) {
-      const int kb = (t % kDecodeStages) * 2 * TILEB;
-      bf16x8 qf[KSTEPS];
+    const int kb = (t % kDecodeStages) * 2 * TILEB;
+    // ---- S^T: element e of s[rs] = sub-tile row 4 kg + e, query column l16 --------------------
+    f32x4 s[RSUB];
 #pragma unroll
-      for (int st = 0; st < KSTEPS; ++st) {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        qf[st] = __builtin_bit_cast(bf16x8, col_ok ? qw[st] : zero);
+    for (int rs = 0; rs < RSUB; ++rs) {
+      s[rs] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int sub = (COLSPLIT ? rs : wave) * 16 * ROWB;
+#pragma unroll
+      for (int st = 0; st < KS; ++st) {
+        const bf16x8 kf = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(lds0 + (kb + sub + k_off[st])));
+        s[rs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, __builtin_bit_cast(bf16x8, qw[st]), s[rs], 0, 0, 0);
       }
-      f32x16 s[2];
-      tile_io.scores(lds0, kb, qf, s);
-      const int row0 = r_lo + kKvTile * t;
-      if (row0 + kKvTile > min_limit) mask_scores(s, limit - row0, hf);
-      bf16x8 pb[4];
-      softmax_step<DT>(s, sc, m_run, l_run, o, pb);
-      tile_io.pv(lds0, kb + TILEB, pb, o);
+    }
+    if (r_lo + kKvTile * (t + 1) > min_limit) {
+#pragma unroll
+      for (int rs = 0; rs < RSUB; ++rs) {
+        const int row0 = r_lo + kKvTile * t + 16 * (COLSPLIT ? rs : wave) + 4 * kg;  // cache row of element 0
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (row0 + e >= limit) s[rs][e] = -INFINITY;
+      }
+    }
+
+    // ---- online softmax of the query column (log2 domain, lazy rescale) -----------------------
+    float mx = -INFINITY;
+#pragma unroll
+    for (int rs = 0; rs < RSUB; ++rs) mx = fmaxf(mx, fmaxf(fmaxf(s[rs][0], s[rs][1]), fmaxf(s[rs][2], s[rs][3])));
+    const float m_cand = max_over_kgroups(mx) * sc;
+    if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleThreshold) != 0) {
+      const float m_new = fmaxf(m_run, m_cand);
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    s16x4 pb[RSUB];
+#pragma unroll
+    for (int rs = 0; rs < RSUB; ++rs) {
+      float p[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(s[rs][e], sc, -m_use));
+      l_run += (p[0] + p[1]) + (p[2] + p[3]);
+      const bf16x4 pv4 = {(bf16_t)p[0], (bf16_t)p[1], (bf16_t)p[2], (bf16_t)p[3]};
+      pb[rs] = __builtin_bit_cast(s16x4, pv4);
+    }
+
+    // ---- O^T[d][q] += V^T P^T: k-slot 4 kg + e of the 16x16x16 MFMA = sub-tile row 4 kg + e -----
+#pragma unroll
+    for (int rs = 0; rs < RSUB; ++rs) {
+      const int sub = (COLSPLIT ? rs : wave) * 16 * ROWB;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(lds0 + (kb + TILEB + sub + v_off[dt])));
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pb[rs], o[dt], 0, 0, 0);
+      }
     }
   }
 
-  // ---- merge the wavefronts that share a query tile ------------------------------------
-  const float l_full = sum_across_halves(l_run);
-  if (hf == 0) m_s[wave][l32] = m_run;
-  __syncthreads();  // also: every wavefront is done with the tile ring
-  float mm = -INFINITY;
+  l_run = sum_over_kgroups(l_run);
+  if constexpr (COLSPLIT) {
+    // every wavefront owns its 16 columns: write the partial straight from registers
+    if (col_ok) {
+      const int64_t prow = ((int64_t)g * a.n_chunks + gc) * a.cols + col;
 #pragma unroll
-  for (int k2 = 0; k2 < KP; ++k2) mm = fmaxf(mm, m_s[k2 * NQS + qs][l32]);
-  const float mu = (mm == -INFINITY) ? 0.f : mm;
-  const float f = __builtin_amdgcn_exp2f(m_run - mu);
-  if (hf == 0) l_s[wave][l32] = l_full * f;
-  float* o_s = reinterpret_cast<float*>(smem);
-#pragma unroll
-  for (int k2 = 0; k2 < KP; ++k2) {
-    if (kp == k2) {
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          float* dst = o_s + (32 * qs + l32) * OPAD + 32 * dt + 8 * vq + 4 * hf;
-          f32x4 val = {o[dt][4 * vq] * f, o[dt][4 * vq + 1] * f, o[dt][4 * vq + 2] * f, o[dt][4 * vq + 3] * f};
-          if (k2 > 0) val += *reinterpret_cast<const f32x4*>(dst);
-          *reinterpret_cast<f32x4*>(dst) = val;
-        }
+      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(a.part_o + prow * D + 16 * dt + 4 * kg) = o[dt];
+      if (kg == 0) {
+        a.part_ml[prow * 2] = m_run;
+        a.part_ml[prow * 2 + 1] = l_run;
+      }
     }
+  } else {
+    // ---- merge the 4 wavefronts (each saw a quarter of the rows) ----------------------------
+    if (kg == 0) m_s[wave][l16] = m_run;
+    __syncthreads();  // also: every wavefront is done with the tile ring
+    const float mm = fmaxf(fmaxf(m_s[0][l16], m_s[1][l16]), fmaxf(m_s[2][l16], m_s[3][l16]));
+    const float mu = (mm == -INFINITY) ? 0.f : mm;
+    const float f = __builtin_amdgcn_exp2f(m_run - mu);
+    if (kg == 0) l_s[wave][l16] = l_run * f;
+    float* o_s = reinterpret_cast<float*>(smem) + wave * (16 * OPAD);  // one region per wavefront
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(o_s + l16 * OPAD + 16 * dt + 4 * kg) = o[dt] * f;
     __syncthreads();
-  }
-
-  const int n_cols = min(QCOLS, a.cols - cb);
-  const int64_t prow0 = ((int64_t)g * a.n_chunks + gc) * a.cols + cb;
-  for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
-    const int cl = idx / (D / 4), d4 = idx % (D / 4);
-    *reinterpret_cast<f32x4*>(a.part_o + (prow0 + cl) * D + 4 * d4) =
-        *reinterpret_cast<const f32x4*>(o_s + cl * OPAD + 4 * d4);
-  }
-  if (tid < n_cols) {
-    const int q2 = tid >> 5, c32 = tid & 31;
-    float m2 = -INFINITY, l2 = 0.f;
-#pragma unroll
-    for (int k2 = 0; k2 < KP; ++k2) {
-      m2 = fmaxf(m2, m_s[k2 * NQS + q2][c32]);
-      l2 += l_s[k2 * NQS + q2][c32];
+    const int n_cols = min(QCOLS, a.cols - blockIdx.y * QCOLS);
+    const int64_t prow0 = ((int64_t)g * a.n_chunks + gc) * a.cols + blockIdx.y * QCOLS;
+    const float* o_all = reinterpret_cast<const float*>(smem);
+    for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
+      const int cl = idx / (D / 4), d4 = idx % (D / 4);
+      const float* src = o_all + cl * OPAD + 4 * d4;
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(src);
+      const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16 * OPAD);
+      const f32x4 v2 = *reinterpret_cast<const f32x4*>(src + 32 * OPAD);
+      const f32x4 v3 = *reinterpret_cast<const f32x4*>(src + 48 * OPAD);
+      *reinterpret_cast<f32x4*>(a.part_o + (prow0 + cl) * D + 4 * d4) = (v0 + v1) + (v2 + v3);
     }
-    a.part_ml[(prow0 + tid) * 2] = m2;
-    a.part_ml[(prow0 + tid) * 2 + 1] = l2;
+    if (tid < n_cols) {
+      a.part_ml[(prow0 + tid) * 2] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
+      a.part_ml[(prow0 + tid) * 2 + 1] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
+    }
   }
 }
 
@@ -323,25 +401,24 @@ __global__ __launch_bounds__(64) void decode_rows_kernel(DecodeArgs a) {
   }
 }
 
-template <int D>
-hipError_t launch_stream(const DecodeArgs& a, hipStream_t s) {
+template <int D, bool COLSPLIT>
+hipError_t launch_stream_mode(const DecodeArgs& a, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, 1>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, COLSPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes<D>());
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, 2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes<D>());
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int qcols = a.cols <= 32 ? 32 : 64;
+  const int qcols = COLSPLIT ? 64 : 16;
   dim3 grid((unsigned)(a.n_chunks * a.Hkv), (unsigned)((a.cols + qcols - 1) / qcols), 1);
-  if (qcols == 32)
-    hipLaunchKernelGGL((decode_stream_kernel<D, 1>), grid, dim3(256), decode_smem_bytes<D>(), s, a);
-  else
-    hipLaunchKernelGGL((decode_stream_kernel<D, 2>), grid, dim3(256), decode_smem_bytes<D>(), s, a);
+  hipLaunchKernelGGL((decode_stream_kernel<D, COLSPLIT>), grid, dim3(256), decode_smem_bytes<D>(), s, a);
   return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_stream(const DecodeArgs& a, hipStream_t s) {
+  return a.cols <= 16 ? launch_stream_mode<D, false>(a, s) : launch_stream_mode<D, true>(a, s);
 }
 
 }  // namespace

@@ -233,6 +233,29 @@ def test_cfg4_decode_full_size():
                 check(got, ref, BF16, "cfg4 block %d step %d %s" % (b, step, "prompt-only remote" if rl is not None else "all cached"))
 
 
+def test_decode_blocks_equals_per_block_calls():
+    N, Hq, Hkv, D, cap, M, H = 4, 8, 2, 128, 200, 4, 2
+    seg = (np.arange(N + 1) * cap).astype(np.int32)
+    lens = np.array([200, 150, 1, 77], dtype=np.int32)
+    g = np.random.default_rng(21)
+    mk = lambda *s: fi.round_to_bf16(g.standard_normal(s).astype(np.float32))
+    q, kc, vc = mk(M, N, Hq, D), mk(M, N * cap, Hkv, D), mk(M, N * cap, Hkv, D)
+    tq, tk, tv = dev(q, BF16), dev(kc, BF16), dev(vc, BF16)
+    p = fa.make_params(N, Hq, Hkv, D, H, BF16)
+    ws = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, N * cap), dtype=torch.uint8, device="cuda")
+    out = torch.full_like(tq, float("nan"))
+    say("decode_blocks M=4 H=2")
+    fa.fedattn_decode_blocks(p, 0, M, tq, tk, tv, out, tq[0].numel(), tk[0].numel(), seg, lens, workspace=ws)
+    torch.cuda.synchronize()
+    for b in range(M):
+        one = torch.full_like(tq[b], float("nan"))
+        fa.fedattn_decode(p, b, tq[b], tk[b], tv[b], one, seg, lens, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(one, out[b]), "decode_blocks differs from fedattn_decode at block %d" % b
+        ref = oracle.decode_step(q[b], kc[b], vc[b], seg, lens, is_sync=oracle.is_sync_block(H, b))
+        check(host(out[b]), ref, BF16, "decode_blocks block %d" % b)
+
+
 # ------------------------------------------------------------------ aggregate
 @pytest.mark.parametrize("dtype", [BF16, F32])
 def test_aggregate_kv_bit_exact(dtype):
