@@ -174,6 +174,7 @@ fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t 
     }
   }
   a.n_q_tiles = (int32_t)tiles;
+  a.n_cus = device_cus();
   if (tiles * a.Hkv * (G / a.heads_per_wg) > 0x7fffffffLL) return fail(FEDATTN_EUNSUPPORTED, "too many query tiles");
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);

@@ -43,6 +43,7 @@ struct PrefillArgs {
   int32_t heads_per_wg;     // MFMA kernel: query heads of one KV group handled by one workgroup
   int32_t q_tile_rows;      // MFMA kernel: query rows per workgroup
   int32_t n_q_tiles;
+  int32_t n_cus;            // compute units of the device (launch shape heuristics)
   float scale;              // softmax scale
   SegLayout seg;
 };

@@ -24,7 +24,7 @@ namespace {
 constexpr int kDecodeStages = 4;
 
 template <int D>
-constexpr int decode_smem_bytes() { return kDecodeStages * 2 * KvTile<D>::TILEB; }
+constexpr int decode_smem_bytes() { return kDecodeStages * 2 * KvTile<D, 0>::TILEB; }
 
 // value of x maximised / summed over the 4 lanes (lane%16 + 16 k) that share a query column
 __device__ inline float max_over_kgroups(float x) {
@@ -47,7 +47,7 @@ __device__ inline float sum_over_kgroups(float x) {
 // wavefront owns its output columns and nothing has to be merged.
 template <int D, bool COLSPLIT>
 __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
-  using TL = KvTile<D>;
+  using TL = KvTile<D, 0>;
   constexpr int KS = D / 32;                 // k-steps of S^T (16x16x32)
   constexpr int DT = D / 16;                 // 16-row tiles of O^T along head_dim
   constexpr int CPR = TL::CPR, ROWB = TL::ROWB, TILEB = TL::TILEB, IPW = TL::IPW;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   int v_off[DT];
   {
     const int vrow = 4 * kg + (l16 >> 2);
-    const int fv = (2 * (vrow & 7)) & (CPR - 1);
+    const int fv = TL::v_swizzle(vrow);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) v_off[dt] = vrow * ROWB + (((2 * dt + ((l16 & 3) >> 1)) ^ fv) * 16) + (l16 & 1) * 8;
   }

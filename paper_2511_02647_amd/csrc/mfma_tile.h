@@ -26,6 +26,7 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units a row maximum may lag be
 // scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier
 #define FEDATTN_SGB_MFMA 0x008
 #define FEDATTN_SGB_DS_READ 0x100
+#define FEDATTN_SGB_VALU 0x402  // vector ALU incl. transcendentals, MFMA excluded
 
 // One direct-to-LDS load: every lane fetches 16 bytes from base + off (bytes) and the
 // wavefront's 1 KB lands at LDS byte address lds_addr (+16 per lane).  base and
@@ -71,7 +72,10 @@ __device__ inline float sum_across_halves(float x) {
   return lo + hi;
 }
 
-template <int D>
+// VSWZ selects the chunk swizzle of V tiles: the transposing reads of the 32x32x16
+// product touch 4 rows x 4 chunks per 32 lanes (VSWZ = 1: f = 4 (row mod 4)), those of the
+// 16x16x16 product 8 rows x 2 chunks (VSWZ = 0: f = 2 (row mod 8)).
+template <int D, int VSWZ>
 struct KvTile {
   static constexpr int KSTEPS = D / 16;         // MFMA k-steps of S^T = K Q^T
   static constexpr int DT = D / 32;             // 32-row tiles of O^T along head_dim
@@ -83,8 +87,12 @@ struct KvTile {
 
   // HBM -> LDS: one load instruction moves 64 x 16 bytes to 1 KB of consecutive LDS
   // (lane l lands at +16 l).  LDS slot (row, cp) receives chunk cp ^ f(row) of the row:
-  // f = row mod CPR for K (conflict-free 16-byte reads down 16 rows), f = 2 (row mod 8)
-  // for V (conflict-free 8-byte transposing reads across 4 rows).
+  // f = row mod CPR for K (conflict-free 16-byte reads down 16 rows), v_swizzle(row) for V
+  // (conflict-free 8-byte transposing reads).
+  static __device__ __attribute__((always_inline)) int v_swizzle(int row) {
+    if (VSWZ == 0) return (2 * (row & 7)) & (CPR - 1);
+    return CPR >= 16 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
+  }
   int dma_row[IPW];        // tile row this lane fetches in its wave's i-th instruction
   int dma_kcol[IPW];       // element offset of the K chunk inside the row
   int dma_vcol[IPW];       // element offset of the V chunk inside the row
@@ -111,7 +119,7 @@ struct KvTile {
       const int row = sidx / CPR, cp = sidx % CPR;
       dma_row[i] = row;
       dma_kcol[i] = (cp ^ (row & (CPR - 1))) * 8;
-      dma_vcol[i] = (cp ^ ((2 * (row & 7)) & (CPR - 1))) * 8;
+      dma_vcol[i] = (cp ^ v_swizzle(row)) * 8;
       dma_koff[i] = (uint32_t)(row * row_elems + dma_kcol[i]) * 2u;
       dma_voff[i] = (uint32_t)(row * row_elems + dma_vcol[i]) * 2u;
     }
@@ -119,7 +127,7 @@ struct KvTile {
     for (int st = 0; st < KSTEPS; ++st) k_off[st] = l32 * ROWB + (((2 * st + hf) ^ (l32 & (CPR - 1))) * 16);
     const int i16 = lane & 15, e = i16 >> 2, c = i16 & 3, dsel = (lane >> 4) & 1;
     const int vrow = 4 * hf + e;
-    const int fv = (2 * (vrow & 7)) & (CPR - 1);
+    const int fv = v_swizzle(vrow);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
       v_off[dt] = vrow * ROWB + (((4 * dt + 2 * dsel + (c >> 1)) ^ fv) * 16) + (c & 1) * 8;
@@ -145,7 +153,10 @@ struct KvTile {
   }
 
   // S^T[kv][q] = K Q^T from the K stage at LDS byte offset kb.  LDS reads run 3 k-steps
-  // ahead of the MFMAs that consume them.
+  // ahead of the MFMAs that consume them.  VALU_PER_STEP > 0 asks the scheduler to place
+  // that many independent vector-ALU instructions of the surrounding code (the softmax
+  // of the previous tile) after each k-step's pair of MFMAs.
+  template <int VALU_PER_STEP = 0>
   __device__ __attribute__((always_inline)) void scores(lds_cptr lds0, int kb, const bf16x8 (&qf)[KSTEPS],
                                                         f32x16 (&s)[2]) const {
 #pragma unroll
@@ -169,8 +180,13 @@ struct KvTile {
     for (int st = 0; st < KSTEPS - kLook; ++st) {
       __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_MFMA, 2, 0);
       __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_DS_READ, 2, 0);
+      if constexpr (VALU_PER_STEP > 0) __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_VALU, VALU_PER_STEP, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_MFMA, 2 * kLook, 0);
+#pragma unroll
+    for (int st = 0; st < kLook; ++st) {
+      __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_MFMA, 2, 0);
+      if constexpr (VALU_PER_STEP > 0) __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_VALU, VALU_PER_STEP, 0);
+    }
   }
 
   // O^T[d][q] += V^T P^T from the V stage at LDS byte offset vb; k-step kk covers tile
@@ -216,14 +232,15 @@ __device__ __attribute__((always_inline)) inline void mask_scores(f32x16 (&s)[2]
       if (32 * aa + 8 * (e >> 2) + (e & 3) >= limh) s[aa][e] = -INFINITY;
 }
 
-// One online-softmax step in the log2 domain on the scores of one tile: updates the
-// running maximum m_run lazily (the accumulators are rescaled only when some row's
-// maximum has grown by more than the threshold; exact, because numerator and
-// denominator of the final division refer to the same value), adds this lane's share
-// of the row sum to l_run and leaves P^T in bf16 in pb.
+// Online softmax in the log2 domain on the scores of one tile, in two parts so that
+// independent matrix work can be issued between them.
+// Part 1: row maxima; updates the running maximum m_run lazily (the accumulators are
+// rescaled only when some row's maximum has grown by more than the threshold; exact,
+// because numerator and denominator of the final division refer to the same value).
+// Returns the reference value the exponentials of this tile use.
 template <int DT>
-__device__ __attribute__((always_inline)) inline void softmax_step(const f32x16 (&s)[2], float sc, float& m_run,
-                                                                    float& l_run, f32x16 (&o)[DT], bf16x8 (&pb)[4]) {
+__device__ __attribute__((always_inline)) inline float softmax_max(const f32x16 (&s)[2], float sc, float& m_run,
+                                                                   float& l_run, f32x16 (&o)[DT]) {
   float mx0 = fmaxf(s[0][0], s[1][0]);
   float mx1 = fmaxf(s[0][1], s[1][1]);
 #pragma unroll
@@ -241,7 +258,13 @@ __device__ __attribute__((always_inline)) inline void softmax_step(const f32x16 
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
   }
-  const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+  return (m_run == -INFINITY) ? 0.f : m_run;
+}
+
+// Part 2: exponentials; adds this lane's share of the row sum to l_run and leaves P^T
+// in bf16 in pb.
+__device__ __attribute__((always_inline)) inline void softmax_exp(const f32x16 (&s)[2], float sc, float m_use,
+                                                                   float& l_run, bf16x8 (&pb)[4]) {
   float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
   for (int aa = 0; aa < 2; ++aa)
@@ -255,6 +278,14 @@ __device__ __attribute__((always_inline)) inline void softmax_step(const f32x16 
       pb[aa * 2 + (e >> 3)][(e & 7) + 1] = (bf16_t)p1;
     }
   l_run += ps0 + ps1;
+}
+
+// Both parts back to back.
+template <int DT>
+__device__ __attribute__((always_inline)) inline void softmax_step(const f32x16 (&s)[2], float sc, float& m_run,
+                                                                    float& l_run, f32x16 (&o)[DT], bf16x8 (&pb)[4]) {
+  const float m_use = softmax_max<DT>(s, sc, m_run, l_run, o);
+  softmax_exp(s, sc, m_use, l_run, pb);
 }
 
 }  // namespace fedattn

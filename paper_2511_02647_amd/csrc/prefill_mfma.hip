@@ -29,25 +29,28 @@ namespace fedattn {
 
 namespace {
 
-#ifndef FEDATTN_PREFILL_OCC
-#define FEDATTN_PREFILL_OCC 2
-#endif
-
-template <int D>
-__global__ __launch_bounds__(256, FEDATTN_PREFILL_OCC) void prefill_mfma_kernel(PrefillArgs a) {
-  using TL = KvTile<D>;
+// NG = 1: 4 wavefronts per workgroup (two workgroups share a CU when the grid is large
+// enough, and one's matrix work overlaps the other's softmax: a single wavefront cannot
+// overlap its own vector ALU work with its own MFMAs).  NG = 2, for grids that would
+// leave one workgroup per CU: 8 wavefronts = two groups of 4 on the same query rows;
+// group g takes the KV tiles j with j mod 2 == g through its own LDS stages and the two
+// partial results are merged at the end (split-KV inside the workgroup).
+template <int D, int NG>
+__global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a) {
+  using TL = KvTile<D, 1>;
   constexpr int KSTEPS = TL::KSTEPS, DT = TL::DT, TILEB = TL::TILEB;
-  // K and V tiles are double-buffered: tile j lives in stage j&1.
-  // Layout: K stage 0, K stage 1, V stage 0, V stage 1 (TILEB bytes each).
-  __shared__ __attribute__((aligned(1024))) unsigned char kv_lds[4 * TILEB];
-  const lds_cptr lds0 = (lds_cptr)(lds_void_ptr)kv_lds;
-  const uint32_t lds_base = lds_addr_of(kv_lds);
-
+  // Per group: K and V tiles double-buffered; the group's i-th tile lives in stage i&1.
+  // Layout per group: K stage 0, K stage 1, V stage 0, V stage 1 (TILEB bytes each).
+  extern __shared__ __attribute__((aligned(1024))) unsigned char kv_lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave_all >> 2;   // wavefront group (KV tile parity)
+  const int wave = wave_all & 3;   // wavefront inside the group
   const int l32 = lane & 31;
   const int hf = lane >> 5;
+  const lds_cptr lds0 = (lds_cptr)(lds_void_ptr)kv_lds + grp * 4 * TILEB;
+  const uint32_t lds_base = lds_addr_of(kv_lds) + grp * 4 * TILEB;
 
   const int Hq = a.Hq, Hkv = a.Hkv;
   const int G = Hq / Hkv;
@@ -166,58 +169,86 @@ __global__ __launch_bounds__(256, FEDATTN_PREFILL_OCC) void prefill_mfma_kernel(
     float m_run = -INFINITY;  // row maximum the accumulators refer to, log2 domain
     float l_run = 0.f;        // this lane's share of the row sum
 
-    // ---- prologue: K and V tile 0 into stage 0 -----------------------------------------
+    // ---- prologue: this group's first K and V tile into its stage 0 ---------------------------
+    const int n_it = (nt + NG - 1) / NG;  // iterations of the workgroup (uniform: they carry barriers)
     __syncthreads();  // the previous query tile of this workgroup is done with LDS
-    {
+    if (grp < nt) {
       int kv0, len;
       bool ct;
-      tile_desc(0, kv0, len, ct);
+      tile_desc(grp, kv0, len, ct);
       tile_io.template dma<false>(kp + (int64_t)kv0 * row_elems, lds_base, len);
       tile_io.template dma<true>(vp + (int64_t)kv0 * row_elems, lds_base + 2 * TILEB, len);
     }
     wait_vmcnt<0>();
     __syncthreads();
 
-    // ---- main loop: tile j is computed from stage j&1 while tile j+1 streams into the
-    // other stage; the two wavefronts that share a SIMD overlap one's matrix work with
-    // the other's softmax ------------------------------------------------------------------
-    for (int j = 0; j < nt; ++j) {
-      const int st_cur = (j & 1) * TILEB;
+    // ---- main loop: the group's i-th tile is computed from stage i&1 while its next tile
+    // streams into the other stage ------------------------------------------------------------
+    for (int it = 0; it < n_it; ++it) {
+      const int j = it * NG + grp;
+      const int st_cur = (it & 1) * TILEB;
       const int st_nxt = TILEB - st_cur;
-      int kv0, len;
-      bool causal_tile;
-      tile_desc(j, kv0, len, causal_tile);
-      if (j + 1 < nt) {
+      if (j + NG < nt) {
         int kv1, len1;
         bool ct1;
-        tile_desc(j + 1, kv1, len1, ct1);
+        tile_desc(j + NG, kv1, len1, ct1);
         tile_io.template dma<false>(kp + (int64_t)kv1 * row_elems, lds_base + st_nxt, len1);
         tile_io.template dma<true>(vp + (int64_t)kv1 * row_elems, lds_base + 2 * TILEB + st_nxt, len1);
       }
 
-      f32x16 s_cur[2];
-      tile_io.scores(lds0, st_cur, qf, s_cur);
+      if (j < nt) {
+        int kv0, len;
+        bool causal_tile;
+        tile_desc(j, kv0, len, causal_tile);
+        f32x16 s_cur[2];
+        tile_io.scores(lds0, st_cur, qf, s_cur);
 
-      if (len < kKvTile || (causal_tile && kv0 + kKvTile - 1 > row0w)) {
-        // valid kv rows of this tile for this lane's query: [0, lim)
-        int lim = len;
-        if (causal_tile) lim = min(lim, my_row - kv0 + 1);
-        mask_scores(s_cur, lim, hf);
+        if (len < kKvTile || (causal_tile && kv0 + kKvTile - 1 > row0w)) {
+          // valid kv rows of this tile for this lane's query: [0, lim)
+          int lim = len;
+          if (causal_tile) lim = min(lim, my_row - kv0 + 1);
+          mask_scores(s_cur, lim, hf);
+        }
+
+        bf16x8 pb[4];
+        softmax_step<DT>(s_cur, sc, m_run, l_run, o, pb);
+
+        tile_io.pv(lds0, 2 * TILEB + st_cur, pb, o);
       }
-
-      bf16x8 pb[4];
-      softmax_step<DT>(s_cur, sc, m_run, l_run, o, pb);
-
-      tile_io.pv(lds0, 2 * TILEB + st_cur, pb, o);
 
       wait_vmcnt<0>();
       __syncthreads();
     }
 
+    if constexpr (NG == 2) {
+      // ---- merge the two groups: group 1 hands (m, l, O) to group 0 through LDS -------------
+      float* xch = reinterpret_cast<float*>(kv_lds) + wave * (66 * 64) + lane;  // [wave][66 values][lane]
+      if (grp == 1) {
+        xch[0] = m_run;
+        xch[64] = l_run;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) xch[(2 + 16 * dt + e) * 64] = o[dt][e];
+      }
+      __syncthreads();
+      if (grp == 0) {
+        const float m1 = xch[0], l1 = xch[64];
+        const float mm = fmaxf(m_run, m1);
+        const float mu = (mm == -INFINITY) ? 0.f : mm;
+        const float f0 = __builtin_amdgcn_exp2f(m_run - mu), f1 = __builtin_amdgcn_exp2f(m1 - mu);
+        l_run = l_run * f0 + l1 * f1;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[dt][e] = o[dt][e] * f0 + xch[(2 + 16 * dt + e) * 64] * f1;
+      }
+    }
+
     // ---- normalise and write ---------------------------------------------------------
     const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (my_row < seg_hi) {
+    if (grp == 0 && my_row < seg_hi) {
       uint16_t* orow = op + ((int64_t)my_row * Hq + head) * D + 4 * hf;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -281,6 +312,20 @@ __global__ __launch_bounds__(kMaxP) void build_kept_tiles_kernel(PrefillArgs a, 
 
 }  // namespace
 
+template <int D, int NG>
+hipError_t launch_prefill_mfma_t(const PrefillArgs& a, dim3 grid, hipStream_t s) {
+  constexpr int smem = NG * 4 * KvTile<D, 1>::TILEB;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<D, NG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((prefill_mfma_kernel<D, NG>), grid, dim3(256 * NG), smem, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s) {
   if (a.n_q_tiles == 0 || n_blocks == 0) return hipSuccess;
   const int G = a.Hq / a.Hkv;
@@ -288,11 +333,10 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s
   // needs at least as many workgroups as the sequence-wide pairing of a sync block
   const int wg_tiles = a.causal ? a.seg.pair_cum[a.seg.n] : a.n_q_tiles;
   dim3 grid((unsigned)(wg_tiles * a.Hkv * (G / a.heads_per_wg)), (unsigned)n_blocks, 1);
-  if (a.D == 128)
-    hipLaunchKernelGGL(prefill_mfma_kernel<128>, grid, dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL(prefill_mfma_kernel<64>, grid, dim3(256), 0, s, a);
-  return hipGetLastError();
+  // fewer than two 4-wave workgroups per CU: use 8-wave workgroups instead
+  const bool wide = (int64_t)grid.x * grid.y < 2 * (int64_t)a.n_cus;
+  if (a.D == 128) return wide ? launch_prefill_mfma_t<128, 2>(a, grid, s) : launch_prefill_mfma_t<128, 1>(a, grid, s);
+  return wide ? launch_prefill_mfma_t<64, 2>(a, grid, s) : launch_prefill_mfma_t<64, 1>(a, grid, s);
 }
 
 hipError_t launch_build_kept_tiles(const PrefillArgs& a, int2* kept_tiles, int32_t* kept_cum,
