@@ -36,6 +36,14 @@ import paper_2511_02647_amd as fa  # noqa: E402
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters' reading for the plain-copy kernel aggregate_kv_kernel
+# (profiles/hbm_traffic_pmc_cfg2_prefill_cfg4_decode.txt).
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_llama8b_prefill": (24661 + 16384) * 1024.0,   # prefill_mfma_kernel, per block launch
+    "cfg4_decode": (73801 + 2470) * 1024.0,             # decode_stream_kernel, mean over local/sync block-steps
+}
+
 
 def log(msg: str) -> None:
     print("[bench] " + msg, file=sys.stderr, flush=True)
@@ -287,7 +295,7 @@ def main() -> int:
     sync_idx = [b for b in range(pb.M) if pb.sync[b]]
     loc_idx = [b for b in range(pb.M) if not pb.sync[b]]
     roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(pb.w.name),
             "kernel": "prefill_mfma_kernel<128>", "launches_per_step": pb.M,
             "avg_launch_us": float(ms.mean() * 1e3),
             "avg_local_us": float(ms[:, loc_idx].mean() * 1e3) if loc_idx else None,
@@ -339,7 +347,7 @@ def main() -> int:
                "end_to_end_GBps": total_bytes / wall / 1e9,
                "ms_per_decode_step": wall / len(steps) * 1e3,
                "roofline": {"bound": "hbm", "achieved": gbs(ms_all), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                            "frac": gbs(ms_all) / PEAK_HBM_GBS, "traffic": None,
+                            "frac": gbs(ms_all) / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(db.w.name),
                             "kernel": "decode_stream_kernel + decode_combine_kernel (per block-step, HIP events)",
                             "avg_block_step_us": ms_all * 1e3 / n_launch,
                             "local_GBps": gbs(ms_loc), "sync_GBps": gbs(ms_syn),
