@@ -133,6 +133,60 @@ def test_prefill_blocks_batched_equals_per_block():
         check(host(out[b]), ref, BF16, "batched block %d" % b)
 
 
+# ------------------------------------- variable sync schedules, exclusion, token-granular exchange
+def test_variable_sync_schedules():
+    # Theorem 3 / "where to perform global attention": any set of sync blocks; the four
+    # placements of the experiments (4 global blocks among M = 8)
+    seg = np.array([0, 64, 150, 260], dtype=np.int32)
+    M, Hq, Hkv, D = 8, 8, 2, 128
+    w = fi.workload("cfg2_llama8b_prefill")
+    blocks = [fi.prefill_block(w, b, total=260) for b in range(M)]
+    schedules = {"shallow-half": [0, 1, 2, 3], "deep-half": [4, 5, 6, 7],
+                 "progressive": [0, 1, 3, 7], "regressive": [0, 4, 6, 7]}
+    refs = {}
+    for name, sync_blocks in schedules.items():
+        for b in range(M):
+            sync = b in sync_blocks
+            say("schedule %s block %d (%s)" % (name, b, "sync" if sync else "local"))
+            got = prefill(*[x[:, :Hq if i == 0 else Hkv] for i, x in enumerate(blocks[b])], seg, Hq=Hq, Hkv=Hkv, D=D,
+                          H=4, block=b, dtype=BF16, sync_override=int(sync))
+            if (b, sync) not in refs:
+                q, k, v = blocks[b]
+                refs[(b, sync)] = oracle.attend_block(q[:, :Hq], k[:, :Hkv], v[:, :Hkv], seg, is_sync=sync)
+            check(got, refs[(b, sync)], BF16, "%s block %d" % (name, b))
+
+
+def test_participant_exclusion_and_token_granular_exchange():
+    seg = np.array([0, 128, 256, 448], dtype=np.int32)
+    Hq, Hkv, D = 8, 2, 128
+    q, k, v = rand_block(31, 448, Hq, Hkv, D)
+    # pi_n = 0 for participant 1: its rows never reach the others (64-token chunks, MFMA path)
+    flags = np.array([1, 1, 0, 0, 1, 1, 1], dtype=np.uint8)
+    kt = oracle.expand_keep_chunks(flags, seg, 64)
+    say("participant 1 excluded from the aggregation")
+    got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, keep_chunks=flags, chunk_tokens=64)
+    check(got, oracle.attend_block(q, k, v, seg, is_sync=True, keep_tok=kt), BF16, "participant excluded")
+    # token-granular random exchange (chunk = 1 token, general kernel)
+    tok = (np.random.default_rng(5).random(448) < 0.3).astype(np.uint8)
+    say("token-granular sparse exchange")
+    got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, keep_chunks=tok, chunk_tokens=1)
+    check(got, oracle.attend_block(q, k, v, seg, is_sync=True, keep_tok=tok), BF16, "token-granular exchange")
+
+
+def test_sparse_local_attention_by_gather():
+    # sparse local attention: each participant keeps a sampled subset of its tokens before the
+    # local computation; the operator then runs on the gathered (shorter) segments
+    seg = np.array([0, 200, 520], dtype=np.int32)
+    Hq, Hkv, D = 8, 2, 128
+    q, k, v = rand_block(32, 520, Hq, Hkv, D)
+    g = np.random.default_rng(6)
+    keep = np.sort(np.concatenate([g.choice(200, 120, replace=False), 200 + g.choice(320, 150, replace=False)]))
+    seg2 = np.array([0, 120, 270], dtype=np.int32)
+    say("sparse local attention (gathered tokens)")
+    got = prefill(q[keep], k[keep], v[keep], seg2, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16)
+    check(got, oracle.attend_block(q[keep], k[keep], v[keep], seg2, is_sync=False), BF16, "sparse local attention")
+
+
 # ------------------------------------------------------------- full-size configs
 def _sampled_check(q, k, v, seg, got, *, is_sync, n_random, what, keep_tok=None, salt=0):
     rows, heads = fi.sample_rows(seg, q.shape[1], n_random, fi.DEFAULT_SEED, salt=salt)
