@@ -20,6 +20,7 @@
 //                 segment up to the diagonal.
 // Tiles entirely above the diagonal or in other participants' segments of a local
 // block are never visited; only diagonal and ragged tiles apply an element mask.
+#include <climits>
 #include <type_traits>
 
 #include "common.h"
@@ -60,6 +61,34 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
   const int N = a.seg.n;
   const int T = a.n_q_tiles;
 
+  // The segment tables sit in the kernel-argument buffer.  Walking them entry by entry costs
+  // one scalar-cache miss after another while nothing else is in flight, so every lane
+  // fetches the entries of segment `lane` (and `lane + 64`) of all tables in one go and the
+  // searches below run on ballots.  Entry 0 of every table is 0.
+  struct Tab {
+    int lo, hi;  // table[lane + 1], table[lane + 65]; INT_MAX past the last segment
+  };
+  auto load_tab = [&](const int32_t* t) __attribute__((always_inline)) {
+    Tab r;
+    r.lo = lane < N ? t[lane + 1] : INT_MAX;
+    r.hi = (N > 64 && lane + 64 < N) ? t[lane + 65] : INT_MAX;
+    return r;
+  };
+  // table[idx] for a wave-uniform idx in [0, N]
+  auto tab_at = [&](const Tab& t, int idx) __attribute__((always_inline)) {
+    if (idx == 0) return 0;
+    return idx <= 64 ? __builtin_amdgcn_readlane(t.lo, idx - 1) : __builtin_amdgcn_readlane(t.hi, idx - 65);
+  };
+  // number of segments s with x >= table[s + 1], i.e. the segment a cumulative index falls in
+  auto tab_find = [&](const Tab& t, int x) __attribute__((always_inline)) {
+    int n = __builtin_popcountll(__builtin_amdgcn_ballot_w64(x >= t.lo));
+    if (N > 64) n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x >= t.hi));
+    return n;
+  };
+  const Tab seg_tab = load_tab(a.seg.seg_off);
+  const Tab tile_tab = load_tab(a.seg.tile_cum);
+  const Tab pair_tab = load_tab(a.seg.pair_cum);
+
   // workgroup -> (kv head, head subgroup, query tile pair); kv head fastest so that the
   // workgroups of one KV head land on one XCD (8 XCDs, round-robin dispatch) and its
   // K/V stay in that XCD's L2; heaviest work first.
@@ -87,11 +116,10 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     tile_a = T - 1 - p;
     if (p < T - 1 - p) tile_b = p;
   } else {
-    if (p >= a.seg.pair_cum[N]) return;
-    int n = 0;
-    while (p >= a.seg.pair_cum[n + 1]) ++n;
-    const int pi = p - a.seg.pair_cum[n];
-    const int t0 = a.seg.tile_cum[n], tn = a.seg.tile_cum[n + 1] - t0;
+    if (p >= tab_at(pair_tab, N)) return;
+    const int n = tab_find(pair_tab, p);
+    const int pi = p - tab_at(pair_tab, n);
+    const int t0 = tab_at(tile_tab, n), tn = tab_at(tile_tab, n + 1) - t0;
     tile_a = t0 + tn - 1 - pi;
     if (pi < tn - 1 - pi) tile_b = t0 + pi;
   }
@@ -106,23 +134,18 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
   TL tile_io;
   tile_io.init(lane, wave, row_elems);
 
-  for (int part = 0; part < 2; ++part) {
-    const int tile = part == 0 ? tile_a : tile_b;
-    if (tile < 0) break;
-
-    int n = 0;
-    while (tile >= a.seg.tile_cum[n + 1]) ++n;
-    const int seg_lo = a.seg.seg_off[n];
-    const int seg_hi = a.seg.seg_off[n + 1];
-    const int q0 = seg_lo + (tile - a.seg.tile_cum[n]) * BM;
-    const int head = g * G + hsub * HS + (wave % HS);
-    const int row0w = q0 + kWaveRows * (wave / HS);
-    const int my_row = row0w + l32;
-    const int row_ld = min(my_row, seg_hi - 1);
-    const int i_last = min(q0 + BM, seg_hi) - 1;
-
-    // KV tile schedule of this query tile: two runs of the kept-tile list, then a
-    // dense range.
+  // One query tile's walk through its KV tiles (all members wave-uniform): two runs of
+  // the kept-tile list, then a dense range [dlo, dhi).
+  struct Walk {
+    int seg_hi, row0w, la_n, lb0, n_list, dlo, dhi, nt;
+  };
+  auto make_walk = [&](int tile, Walk& w) __attribute__((always_inline)) {
+    const int n = tab_find(tile_tab, tile);
+    const int seg_lo = tab_at(seg_tab, n);
+    w.seg_hi = tab_at(seg_tab, n + 1);
+    const int q0 = seg_lo + (tile - tab_at(tile_tab, n)) * BM;
+    w.row0w = q0 + kWaveRows * (wave / HS);
+    const int i_last = min(q0 + BM, w.seg_hi) - 1;
     int la_n = 0, lb0 = 0, lb_n = 0;
     if (sparse) {
       la_n = a.kept_cum[n];
@@ -131,36 +154,68 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
         lb_n = a.kept_cum[N] - lb0;
       }
     }
-    const int n_list = la_n + lb_n;
-    const int dlo = (is_sync && !sparse) ? 0 : seg_lo;
-    const int dhi = causal ? i_last + 1 : ((is_sync && !sparse) ? a.total : seg_hi);
-    const int n_dense = (dhi - dlo + kKvTile - 1) / kKvTile;
-    const int nt = n_list + n_dense;
-
-    auto tile_desc = [&](int it, int& kv0, int& len, bool& causal_tile) __attribute__((always_inline)) {
-      if (it < n_list) {
-        const int idx = it < la_n ? it : lb0 + (it - la_n);
-        const int2 t = a.kept_tiles[idx];
-        kv0 = __builtin_amdgcn_readfirstlane(t.x);
-        len = __builtin_amdgcn_readfirstlane(t.y);
-        causal_tile = false;
-      } else {
-        kv0 = dlo + kKvTile * (it - n_list);
-        len = min(kKvTile, dhi - kv0);
-        causal_tile = causal;
-      }
-    };
-
-    // Q fragments (B operand of S^T): lane (q row = l32, half hf) holds
-    // Q[row][16*step + 8*hf .. +8].
-    bf16x8 qf[KSTEPS];
-    {
-      const uint16_t* qrow = qp + ((int64_t)row_ld * Hq + head) * D + 8 * hf;
-#pragma unroll
-      for (int st = 0; st < KSTEPS; ++st)
-        qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + 16 * st));
+    w.la_n = la_n;
+    w.lb0 = lb0;
+    w.n_list = la_n + lb_n;
+    w.dlo = (is_sync && !sparse) ? 0 : seg_lo;
+    w.dhi = causal ? i_last + 1 : ((is_sync && !sparse) ? a.total : w.seg_hi);
+    w.nt = w.n_list + (w.dhi - w.dlo + kKvTile - 1) / kKvTile;  // >= 1: the tile has a row
+  };
+  auto tile_desc = [&](const Walk& w, int it, int& kv0, int& len, bool& causal_tile)
+                       __attribute__((always_inline)) {
+    if (it < w.n_list) {
+      const int idx = it < w.la_n ? it : w.lb0 + (it - w.la_n);
+      const int2 t = a.kept_tiles[idx];
+      kv0 = __builtin_amdgcn_readfirstlane(t.x);
+      len = __builtin_amdgcn_readfirstlane(t.y);
+      causal_tile = false;
+    } else {
+      kv0 = w.dlo + kKvTile * (it - w.n_list);
+      len = min(kKvTile, w.dhi - kv0);
+      causal_tile = causal;
     }
+  };
+  // K and V tile `it` of walk w into the stage at byte offset st of this group
+  auto fetch_tile = [&](const Walk& w, int it, int st) __attribute__((always_inline)) {
+    int kv0, len;
+    bool ct;
+    tile_desc(w, it, kv0, len, ct);
+    tile_io.template dma<false>(kp + (int64_t)kv0 * row_elems, lds_base + st, len);
+    tile_io.template dma<true>(vp + (int64_t)kv0 * row_elems, lds_base + 2 * TILEB + st, len);
+  };
+  const int head = g * G + hsub * HS + (wave % HS);
+  // Q fragments (B operand of S^T): lane (q row = l32, half hf) holds
+  // Q[row][16*step + 8*hf .. +8].
+  auto load_q = [&](const Walk& w, bf16x8 (&qf)[KSTEPS]) __attribute__((always_inline)) {
+    const int row_ld = min(w.row0w + l32, w.seg_hi - 1);
+    const uint16_t* qrow = qp + ((int64_t)row_ld * Hq + head) * D + 8 * hf;
+#pragma unroll
+    for (int st = 0; st < KSTEPS; ++st)
+      qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + 16 * st));
+  };
 
+  // The workgroup's walks run as one pipeline: the stage parity carries on from the
+  // first walk into the second, whose first tile and Q fragments are fetched while
+  // the first walk finishes.
+  Walk cur, nxt;
+  make_walk(tile_a, cur);
+  bf16x8 qf[KSTEPS];
+  load_q(cur, qf);
+  if (grp < cur.nt) fetch_tile(cur, grp, 0);
+  nxt = cur;
+  const bool two = tile_b >= 0;
+  unsigned warm = 0;
+  if (two) {
+    make_walk(tile_b, nxt);
+    // pull the second walk's Q rows into L2 now (one dword per 128-byte line)
+    const int row_ld = min(nxt.row0w + l32, nxt.seg_hi - 1);
+    warm = *reinterpret_cast<const unsigned*>(qp + ((int64_t)row_ld * Hq + head) * D + (hf * 64) % D);
+  }
+  int git = 0;  // iterations this workgroup has run: stage of an iteration = git & 1
+
+  for (int part = 0;; ++part) {
+    const bool more = part == 0 && two;
+    const int my_row = cur.row0w + l32;
     f32x16 o[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -169,41 +224,31 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     float m_run = -INFINITY;  // row maximum the accumulators refer to, log2 domain
     float l_run = 0.f;        // this lane's share of the row sum
 
-    // ---- prologue: this group's first K and V tile into its stage 0 ---------------------------
-    const int n_it = (nt + NG - 1) / NG;  // iterations of the workgroup (uniform: they carry barriers)
-    __syncthreads();  // the previous query tile of this workgroup is done with LDS
-    if (grp < nt) {
-      int kv0, len;
-      bool ct;
-      tile_desc(grp, kv0, len, ct);
-      tile_io.template dma<false>(kp + (int64_t)kv0 * row_elems, lds_base, len);
-      tile_io.template dma<true>(vp + (int64_t)kv0 * row_elems, lds_base + 2 * TILEB, len);
-    }
+    const int n_it = (cur.nt + NG - 1) / NG;  // iterations of the workgroup (uniform: they carry barriers)
     wait_vmcnt<0>();
+    if (part == 0) asm volatile("" ::"v"(warm));
     __syncthreads();
 
-    // ---- main loop: the group's i-th tile is computed from stage i&1 while its next tile
-    // streams into the other stage ------------------------------------------------------------
-    for (int it = 0; it < n_it; ++it) {
+    // ---- main loop: the group's i-th tile is computed from one stage while its next tile
+    // (in the last iteration: the first tile of the next walk) streams into the other ---------
+    for (int it = 0; it < n_it; ++it, ++git) {
       const int j = it * NG + grp;
-      const int st_cur = (it & 1) * TILEB;
+      const int st_cur = (git & 1) * TILEB;
       const int st_nxt = TILEB - st_cur;
-      if (j + NG < nt) {
-        int kv1, len1;
-        bool ct1;
-        tile_desc(j + NG, kv1, len1, ct1);
-        tile_io.template dma<false>(kp + (int64_t)kv1 * row_elems, lds_base + st_nxt, len1);
-        tile_io.template dma<true>(vp + (int64_t)kv1 * row_elems, lds_base + 2 * TILEB + st_nxt, len1);
+      if (it + 1 < n_it) {
+        if (j + NG < cur.nt) fetch_tile(cur, j + NG, st_nxt);
+      } else if (more && grp < nxt.nt) {
+        fetch_tile(nxt, grp, st_nxt);
       }
 
-      if (j < nt) {
+      if (j < cur.nt) {
         int kv0, len;
         bool causal_tile;
-        tile_desc(j, kv0, len, causal_tile);
+        tile_desc(cur, j, kv0, len, causal_tile);
         f32x16 s_cur[2];
         tile_io.scores(lds0, st_cur, qf, s_cur);
 
-        if (len < kKvTile || (causal_tile && kv0 + kKvTile - 1 > row0w)) {
+        if (len < kKvTile || (causal_tile && kv0 + kKvTile - 1 > cur.row0w)) {
           // valid kv rows of this tile for this lane's query: [0, lim)
           int lim = len;
           if (causal_tile) lim = min(lim, my_row - kv0 + 1);
@@ -220,20 +265,29 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
       __syncthreads();
     }
 
+    // this walk's Q fragments are dead: fetch the next walk's behind the epilogue
+    if (more) load_q(nxt, qf);
+
     if constexpr (NG == 2) {
-      // ---- merge the two groups: group 1 hands (m, l, O) to group 0 through LDS -------------
-      float* xch = reinterpret_cast<float*>(kv_lds) + wave * (66 * 64) + lane;  // [wave][66 values][lane]
+      // ---- merge the two groups: group 1 hands (m, l, O) to group 0 through LDS.  The K and
+      // V stages of the last iteration are free in both groups (the other stages may be
+      // receiving the next walk's first tiles): wave w gets one of these four buffers.
+      __shared__ float xml[4 * 128];
+      const int st_free = ((git - 1) & 1) * TILEB;
+      f32x4* xo = reinterpret_cast<f32x4*>(kv_lds + (wave >> 1) * 4 * TILEB + (wave & 1) * 2 * TILEB + st_free) + lane;
+      float* xm = xml + wave * 128 + lane;
       if (grp == 1) {
-        xch[0] = m_run;
-        xch[64] = l_run;
+        xm[0] = m_run;
+        xm[64] = l_run;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) xch[(2 + 16 * dt + e) * 64] = o[dt][e];
+          for (int vq = 0; vq < 4; ++vq)
+            xo[(4 * dt + vq) * 64] = f32x4{o[dt][4 * vq], o[dt][4 * vq + 1], o[dt][4 * vq + 2], o[dt][4 * vq + 3]};
       }
       __syncthreads();
       if (grp == 0) {
-        const float m1 = xch[0], l1 = xch[64];
+        const float m1 = xm[0], l1 = xm[64];
         const float mm = fmaxf(m_run, m1);
         const float mu = (mm == -INFINITY) ? 0.f : mm;
         const float f0 = __builtin_amdgcn_exp2f(m_run - mu), f1 = __builtin_amdgcn_exp2f(m1 - mu);
@@ -241,15 +295,24 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) o[dt][e] = o[dt][e] * f0 + xch[(2 + 16 * dt + e) * 64] * f1;
+          for (int vq = 0; vq < 4; ++vq) {
+            const f32x4 x = xo[(4 * dt + vq) * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[dt][4 * vq + e] = o[dt][4 * vq + e] * f0 + x[e] * f1;
+          }
       }
     }
 
-    // ---- normalise and write ---------------------------------------------------------
+    // ---- normalise and write: the wave's 32 x D tile goes through a free LDS stage so
+    // that every store instruction writes whole rows (a lane owns a row in registers, which
+    // written directly would scatter 16-byte pieces over 32 rows per instruction) ----------
     const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (grp == 0 && my_row < seg_hi) {
-      uint16_t* orow = op + ((int64_t)my_row * Hq + head) * D + 4 * hf;
+    if (grp == 0) {
+      constexpr int ROWO = 2 * D, CPR = D / 8, RPI = 64 / CPR;  // row bytes, 16-byte chunks per row, rows per store
+      const int st_free = ((git - 1) & 1) * TILEB;
+      unsigned char* stage = NG == 2 ? kv_lds + (wave >> 1) * 4 * TILEB + (wave & 1) * 2 * TILEB + st_free
+                                     : kv_lds + (wave >> 1) * 2 * TILEB + st_free + (wave & 1) * (TILEB / 2);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -257,9 +320,21 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
           bf16x4 w;
 #pragma unroll
           for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(o[dt][4 * vq + e] * inv);
-          *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * vq) = __builtin_bit_cast(u32x2, w);
+          const int c = 4 * dt + vq;
+          *reinterpret_cast<u32x2*>(stage + l32 * ROWO + ((c ^ (l32 & (CPR - 1))) << 4) + 8 * hf) =
+              __builtin_bit_cast(u32x2, w);
         }
+      const int c = lane % CPR;
+#pragma unroll
+      for (int kk = 0; kk < kWaveRows / RPI; ++kk) {
+        const int r = kk * RPI + lane / CPR;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(stage + r * ROWO + ((c ^ (r & (CPR - 1))) << 4));
+        if (cur.row0w + r < cur.seg_hi)
+          *reinterpret_cast<u32x4*>(op + ((int64_t)(cur.row0w + r) * Hq + head) * D + 8 * c) = w;
+      }
     }
+    if (!more) break;
+    cur = nxt;
   }
 }
 
