@@ -69,9 +69,11 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     int lo, hi;  // table[lane + 1], table[lane + 65]; INT_MAX past the last segment
   };
   auto load_tab = [&](const int32_t* t) __attribute__((always_inline)) {
+    // the tables have kMaxP + 1 entries whatever N is: fetch first (nothing to wait for), select after
+    const int lo = t[lane + 1], hi = t[lane + 65];
     Tab r;
-    r.lo = lane < N ? t[lane + 1] : INT_MAX;
-    r.hi = (N > 64 && lane + 64 < N) ? t[lane + 65] : INT_MAX;
+    r.lo = lane < N ? lo : INT_MAX;
+    r.hi = lane + 64 < N ? hi : INT_MAX;
     return r;
   };
   // table[idx] for a wave-uniform idx in [0, N]
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
       if (it + 1 < n_it) {
         if (j + NG < cur.nt) fetch_tile(cur, j + NG, st_nxt);
       } else if (more && grp < nxt.nt) {
-        fetch_tile(nxt, grp, st_nxt);
+        fetch_tile(nxt, grp, st_nxt);  // last iteration of the first walk: start on the second walk
       }
 
       if (j < cur.nt) {
@@ -265,8 +267,10 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
       __syncthreads();
     }
 
-    // this walk's Q fragments are dead: fetch the next walk's behind the epilogue
-    if (more) load_q(nxt, qf);
+    // This walk's Q fragments are dead: fetch the next walk's behind the epilogue.  With two
+    // groups the hand-over barrier comes first (group 1 has nothing else to do after it;
+    // group 0 loads once it has taken group 1's partial results over).
+    if (NG == 1 && more) load_q(nxt, qf);
 
     if constexpr (NG == 2) {
       // ---- merge the two groups: group 1 hands (m, l, O) to group 0 through LDS.  The K and
@@ -285,7 +289,10 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
           for (int vq = 0; vq < 4; ++vq)
             xo[(4 * dt + vq) * 64] = f32x4{o[dt][4 * vq], o[dt][4 * vq + 1], o[dt][4 * vq + 2], o[dt][4 * vq + 3]};
       }
-      __syncthreads();
+      // LDS-only hand-over: wait for the LDS writes, not for the loads in flight for the next walk
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+      if (grp == 1 && more) load_q(nxt, qf);
       if (grp == 0) {
         const float m1 = xm[0], l1 = xm[64];
         const float mm = fmaxf(m_run, m1);
@@ -300,6 +307,7 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[dt][4 * vq + e] = o[dt][4 * vq + e] * f0 + x[e] * f1;
           }
+        if (more) load_q(nxt, qf);
       }
     }
 
