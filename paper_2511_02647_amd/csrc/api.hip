@@ -106,6 +106,11 @@ size_t prefill_ws_bytes(const fedattn_params* p, int32_t tokens) {
   return kKeptCumBytes + align_up(max_tiles * sizeof(int2), 16);
 }
 
+// chunk counters of the fused combine, one per (KV head, participant), at the end of the workspace
+size_t decode_counter_bytes(const fedattn_params* p) {
+  return align_up((size_t)p->n_kv_heads * (size_t)p->n_participants * 4, 256);
+}
+
 size_t decode_ws_bytes(const fedattn_params* p, int32_t capacity) {
   if (!(p->dtype == FEDATTN_BF16 && (p->head_dim == 64 || p->head_dim == 128))) return 16;
   const size_t G = (size_t)(p->n_q_heads / p->n_kv_heads);
@@ -114,7 +119,7 @@ size_t decode_ws_bytes(const fedattn_params* p, int32_t capacity) {
   static const int forced = env_int("FEDATTN_DECODE_CHUNK", 0);
   const size_t chunks = (forced > 0 ? (size_t)capacity / (size_t)forced + 1 : (size_t)decode_target_chunks(p->n_kv_heads)) + N;
   const size_t rows = (size_t)p->n_kv_heads * chunks * G * N;  // sync blocks: N*G query columns per chunk
-  return align_up(rows * (size_t)p->head_dim * 4, 256) + align_up(rows * 8, 256);
+  return align_up(rows * (size_t)p->head_dim * 4, 256) + align_up(rows * 8, 256) + decode_counter_bytes(p);
 }
 
 fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t n_blocks, const void* q,
@@ -274,6 +279,18 @@ fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block
   const size_t esize = params->dtype == FEDATTN_BF16 ? 2 : 4;
   DecodeArgs args[2];  // [0] local block, [1] sync block: the split differs, the layout does not
   bool built[2] = {false, false};
+  int32_t* counters = nullptr;
+  if (mfma) {
+    const size_t need = decode_ws_bytes(params, capacity);
+    if (!workspace || workspace_bytes < need)
+      return fail(FEDATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need, workspace_bytes);
+    if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
+    // local blocks count their chunks in at the end of the workspace; the counters start at
+    // zero and every launch leaves them at zero for the next one
+    counters = reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(workspace) + need - decode_counter_bytes(params));
+    hipError_t e = launch_decode_zero_counters(counters, params->n_kv_heads * N, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (counters): %s", hipGetErrorString(e));
+  }
   for (int b = 0; b < n_blocks; ++b) {
     const bool sync =
         sync_override >= 0 ? sync_override != 0 : sync_block_rule(params->sync_interval, block_idx0 + b);
@@ -306,16 +323,19 @@ fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block
       }
       a.n_chunks = (int32_t)chunks;
       if (mfma) {
-        const size_t need = decode_ws_bytes(params, capacity);
-        if (!workspace || workspace_bytes < need)
-          return fail(FEDATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need, workspace_bytes);
-        if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
+        const size_t need = decode_ws_bytes(params, capacity) - decode_counter_bytes(params);
         const size_t rows = (size_t)a.Hkv * (size_t)a.n_chunks * (size_t)a.cols;
         const size_t o_bytes = align_up(rows * (size_t)a.D * 4, 256);
-        if (o_bytes + rows * 8 > workspace_bytes)
+        if (o_bytes + rows * 8 > need)
           return fail(FEDATTN_EWORKSPACE, "decode partials (%zu bytes) exceed the workspace", o_bytes + rows * 8);
         a.part_o = reinterpret_cast<float*>(workspace);
         a.part_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + o_bytes);
+        a.counters = counters;
+        // fused combine: the workgroups of a segment write its output rows, so every segment
+        // needs one (an empty segment's zero rows come from the separate combine kernel)
+        bool all_have_rows = true;
+        for (int n = 0; n < N; ++n) all_have_rows = all_have_rows && seg_lens[n] > 0;
+        a.fuse_combine = (!sync && a.cols <= 16 && all_have_rows) ? 1 : 0;
       }
       built[sync ? 1 : 0] = true;
     }

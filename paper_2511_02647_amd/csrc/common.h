@@ -55,6 +55,8 @@ struct DecodeArgs {
   void* out;
   float* part_o;            // [Hkv, n_chunks, cols, D] fp32: sum_j p_j v_j with p_j = 2^(s_j - m), unnormalised
   float* part_ml;           // [Hkv, n_chunks, cols, 2] (m in log2 domain, l)
+  int32_t* counters;        // [Hkv, N] chunks counted in per (KV head, segment); zero before and after a launch
+  int32_t fuse_combine;     // local block with at most 16 query columns: the last chunk of a segment merges
   int32_t N, Hq, Hkv, D;
   int32_t is_sync;
   int32_t chunk_rows;       // cache rows per workgroup
@@ -84,6 +86,7 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s
 hipError_t launch_build_kept_tiles(const PrefillArgs& a, int2* kept_tiles, int32_t* kept_cum,
                                    hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_decode_zero_counters(int32_t* counters, int n, hipStream_t s);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t s);
 
 // Algorithm 1: block m = Ht + h (1-based) is the global-attention block iff h = H.

@@ -74,11 +74,26 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   const int gc = blockIdx.x / Hkv;  // chunk index over all segments
   const int cb = blockIdx.y * QCOLS + (COLSPLIT ? 16 * wave : 0);  // first query column of this wavefront
 
-  int m = 0;
-  while (gc >= a.chunk_cum[m + 1]) ++m;
-  const int c = gc - a.chunk_cum[m];
-  const int own_len = a.seg_lens[m];
-  const int rem_len = a.has_remote ? a.remote_lens[m] : own_len;
+  // The segment tables sit in the kernel-argument buffer; a walk over them would take one
+  // scalar-cache miss after another before the first cache row is requested.  Every lane
+  // fetches the entries of segments `lane` and `lane + 64` at once, the chunk's segment is
+  // found with ballots and its entries are read out of the lanes that hold them.
+  const int N = a.N;
+  const int ck_lo = a.chunk_cum[lane + 1], ck_hi = a.chunk_cum[lane + 65];
+  const int sl_lo = a.seg_lens[lane], sl_hi = a.seg_lens[lane + 64];
+  const int rl_lo = a.remote_lens[lane], rl_hi = a.remote_lens[lane + 64];
+  const int so_lo = a.seg_off[lane], so_hi = a.seg_off[lane + 64];
+  int m = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < N && gc >= ck_lo));
+  if (N > 64) m += __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane + 64 < N && gc >= ck_hi));
+  auto pick = [&](int lo, int hi, int idx) __attribute__((always_inline)) {
+    return idx < 64 ? __builtin_amdgcn_readlane(lo, idx) : __builtin_amdgcn_readlane(hi, idx - 64);
+  };
+  const int chunk0 = m == 0 ? 0 : pick(ck_lo, ck_hi, m - 1);  // first chunk of segment m
+  const int n_seg_chunks = pick(ck_lo, ck_hi, m) - chunk0;
+  const int c = gc - chunk0;
+  const int own_len = pick(sl_lo, sl_hi, m);
+  const int rem_len = a.has_remote ? pick(rl_lo, rl_hi, m) : own_len;
+  const int seg_row0 = pick(so_lo, so_hi, m);
   const bool sync = a.is_sync != 0;
   const int rows_end = sync ? max(own_len, rem_len) : own_len;
   const int min_limit = sync ? min(own_len, rem_len) : own_len;
@@ -87,8 +102,8 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   const int nt = (r_hi - r_lo + kKvTile - 1) / kKvTile;
   const int row_elems = Hkv * D;
 
-  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(a.k_cache) + ((int64_t)(a.seg_off[m] + r_lo) * Hkv + g) * D;
-  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(a.v_cache) + ((int64_t)(a.seg_off[m] + r_lo) * Hkv + g) * D;
+  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(a.k_cache) + ((int64_t)(seg_row0 + r_lo) * Hkv + g) * D;
+  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(a.v_cache) + ((int64_t)(seg_row0 + r_lo) * Hkv + g) * D;
 
   TL tile_io;
   tile_io.init(lane, wave, row_elems);
@@ -249,8 +264,52 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
     for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(o_s + l16 * OPAD + 16 * dt + 4 * kg) = o[dt] * f;
     __syncthreads();
     const int n_cols = min(QCOLS, a.cols - blockIdx.y * QCOLS);
-    const int64_t prow0 = ((int64_t)g * a.n_chunks + gc) * a.cols + blockIdx.y * QCOLS;
+    const int col0 = blockIdx.y * QCOLS;
+    const int64_t prow0 = ((int64_t)g * a.n_chunks + gc) * a.cols + col0;
     const float* o_all = reinterpret_cast<const float*>(smem);
+    // local block with the combine fused in: query column cl is head g G + cl of participant m
+    uint16_t* out_rows = reinterpret_cast<uint16_t*>(a.out) + ((int64_t)m * Hq + g * G + col0) * D;
+    if (a.fuse_combine && n_seg_chunks == 1) {
+      // the segment's only chunk: normalise and write the output rows, no partials
+      for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
+        const int cl = idx / (D / 4), d4 = idx % (D / 4);
+        const float* src = o_all + cl * OPAD + 4 * d4;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(src);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16 * OPAD);
+        const f32x4 v2 = *reinterpret_cast<const f32x4*>(src + 32 * OPAD);
+        const f32x4 v3 = *reinterpret_cast<const f32x4*>(src + 48 * OPAD);
+        const float den = l_s[0][cl] + l_s[1][cl] + l_s[2][cl] + l_s[3][cl];
+        const f32x4 val = ((v0 + v1) + (v2 + v3)) * (den > 0.f ? 1.f / den : 0.f);
+        const bf16x4 w = {(bf16_t)val[0], (bf16_t)val[1], (bf16_t)val[2], (bf16_t)val[3]};
+        *reinterpret_cast<u32x2*>(out_rows + cl * D + 4 * d4) = __builtin_bit_cast(u32x2, w);
+      }
+      return;
+    }
+    if (!a.fuse_combine) {
+      for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
+        const int cl = idx / (D / 4), d4 = idx % (D / 4);
+        const float* src = o_all + cl * OPAD + 4 * d4;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(src);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16 * OPAD);
+        const f32x4 v2 = *reinterpret_cast<const f32x4*>(src + 32 * OPAD);
+        const f32x4 v3 = *reinterpret_cast<const f32x4*>(src + 48 * OPAD);
+        *reinterpret_cast<f32x4*>(a.part_o + (prow0 + cl) * D + 4 * d4) = (v0 + v1) + (v2 + v3);
+      }
+      if (tid < n_cols) {
+        a.part_ml[(prow0 + tid) * 2] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
+        a.part_ml[(prow0 + tid) * 2 + 1] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
+      }
+      return;
+    }
+
+    // ---- fused combine: the workgroup that finishes a segment's last chunk merges them ------
+    // The partials travel between workgroups inside one launch, so they are written and read
+    // with device-scope atomic accesses (coherent at the device whatever caches sit in
+    // between) rather than with plain accesses plus cache-wide write-back and invalidate
+    // fences, which cost far more than the few KB exchanged here.  A workgroup counts itself
+    // in only after all its partial stores have completed (vmcnt = 0 in every wavefront,
+    // then the barrier); the workgroup that finds all other chunks counted in merges and
+    // leaves the counter at zero for the next launch.
     for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
       const int cl = idx / (D / 4), d4 = idx % (D / 4);
       const float* src = o_all + cl * OPAD + 4 * d4;
@@ -258,13 +317,65 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
       const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16 * OPAD);
       const f32x4 v2 = *reinterpret_cast<const f32x4*>(src + 32 * OPAD);
       const f32x4 v3 = *reinterpret_cast<const f32x4*>(src + 48 * OPAD);
-      *reinterpret_cast<f32x4*>(a.part_o + (prow0 + cl) * D + 4 * d4) = (v0 + v1) + (v2 + v3);
+      const f32x4 sum = (v0 + v1) + (v2 + v3);
+      float* dst = a.part_o + (prow0 + cl) * D + 4 * d4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) __hip_atomic_store(dst + e, sum[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tid < n_cols) {
-      a.part_ml[(prow0 + tid) * 2] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
-      a.part_ml[(prow0 + tid) * 2 + 1] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
+      __hip_atomic_store(a.part_ml + (prow0 + tid) * 2,
+                         fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid])), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.part_ml + (prow0 + tid) * 2 + 1, l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid],
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __shared__ int last_s;
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    wait_vmcnt<0>();
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __syncthreads();
+    if (tid == 0) {
+      int* cnt = a.counters + g * N + m;  // at most 16 columns: one workgroup per chunk
+      const int seen = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int last = seen == n_seg_chunks - 1;
+      if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      last_s = last;
+    }
+    __syncthreads();
+    if (!last_s) return;
+    const int64_t crow0 = ((int64_t)g * a.n_chunks + chunk0) * a.cols + col0;  // chunk 0 of the segment, column 0
+    const int64_t cstride = a.cols;                                            // partial rows between chunks
+    for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
+      const int cl = idx / (D / 4), d4 = idx % (D / 4);
+      const float* ml = a.part_ml + (crow0 + cl) * 2;
+      float mm = -INFINITY;
+      for (int cc = 0; cc < n_seg_chunks; ++cc)
+        mm = fmaxf(mm, __hip_atomic_load(ml + cc * cstride * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      const float mu = (mm == -INFINITY) ? 0.f : mm;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      float den = 0.f;
+      const float* po = a.part_o + (crow0 + cl) * D + 4 * d4;
+      for (int cc = 0; cc < n_seg_chunks; ++cc) {
+        const float mc = __hip_atomic_load(ml + cc * cstride * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float lc = __hip_atomic_load(ml + cc * cstride * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float w = __builtin_amdgcn_exp2f(mc - mu);
+        den = fmaf(lc, w, den);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          acc[e] = fmaf(__hip_atomic_load(po + cc * cstride * D + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), w, acc[e]);
+      }
+      const f32x4 val = acc * (den > 0.f ? 1.f / den : 0.f);
+      const bf16x4 w4 = {(bf16_t)val[0], (bf16_t)val[1], (bf16_t)val[2], (bf16_t)val[3]};
+      *reinterpret_cast<u32x2*>(out_rows + cl * D + 4 * d4) = __builtin_bit_cast(u32x2, w4);
     }
   }
+}
+
+// Zeroes the chunk counters of the fused combine (a kernel rather than a memset so that
+// callers may capture the calls in a graph).
+__global__ void decode_zero_counters_kernel(int32_t* counters, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) counters[i] = 0;
 }
 
 // Merges the chunk partials of one (participant, query head) and writes the output row.
@@ -438,8 +549,14 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
     hipError_t e = a.D == 128 ? launch_stream<128>(a, s) : launch_stream<64>(a, s);
     if (e != hipSuccess) return e;
   }
+  if (a.fuse_combine) return hipSuccess;
   hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq)), dim3(a.D <= 64 ? 64 : 128), 0,
                      s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_zero_counters(int32_t* counters, int n, hipStream_t s) {
+  hipLaunchKernelGGL(decode_zero_counters_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, counters, n);
   return hipGetLastError();
 }
 

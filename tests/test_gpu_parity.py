@@ -287,6 +287,29 @@ def test_cfg4_decode_full_size():
                 check(got, ref, BF16, "cfg4 block %d step %d %s" % (b, step, "prompt-only remote" if rl is not None else "all cached"))
 
 
+def test_decode_local_chunk_merge_in_kernel_with_dirty_workspace():
+    """Local blocks merge a segment's chunks inside the streaming kernel, counting chunks in
+    through the workspace: whatever the workspace held before must not matter, and it must be
+    reusable call after call (1, 2 and many chunks per segment)."""
+    N, Hq, Hkv, D, cap = 3, 8, 2, 128, 1000
+    seg = (np.arange(N + 1) * cap).astype(np.int32)
+    lens = np.array([1000, 64, 513], dtype=np.int32)
+    p = fa.make_params(N, Hq, Hkv, D, 0, BF16)
+    nbytes = fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, N * cap)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    _, kc, vc = rand_block(31, N * cap, Hq, Hkv, D, bf16=True)
+    tk, tv = dev(kc, BF16), dev(vc, BF16)
+    for rep in range(3):
+        q, _, _ = rand_block(32 + rep, N, Hq, Hkv, D, bf16=True)
+        tq = dev(q, BF16)
+        out = torch.full_like(tq, float("nan"))
+        say("decode local, dirty workspace, call %d" % rep)
+        fa.fedattn_decode(p, 0, tq, tk, tv, out, seg, lens, sync_override=0, workspace=ws)
+        torch.cuda.synchronize()
+        ref = oracle.decode_step(q, kc, vc, seg, lens, is_sync=False)
+        check(host(out), ref, BF16, "decode local in-kernel merge, call %d" % rep)
+
+
 def test_decode_blocks_equals_per_block_calls():
     N, Hq, Hkv, D, cap, M, H = 4, 8, 2, 128, 200, 4, 2
     seg = (np.arange(N + 1) * cap).astype(np.int32)
