@@ -137,7 +137,9 @@ fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t bloc
  *   remote_lens    host int32[N] or NULL (= seg_lens): rows of segment m that the
  *                  other participants see in a sync block (e.g. the prompt length
  *                  when generated tokens are not exchanged).
- *   workspace      device, >= fedattn_workspace_bytes(DECODE); holds split-KV partials.
+ *   workspace      device, >= fedattn_workspace_bytes(DECODE); holds split-KV partials and
+ *                  chunk counters while the call's kernels run.  What it contains on entry
+ *                  does not matter; calls that share a workspace must be ordered (same stream).
  */
 fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q,
                               const void* k_cache, const void* v_cache, void* out,

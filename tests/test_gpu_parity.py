@@ -141,12 +141,13 @@ def test_variable_sync_schedules():
     M, Hq, Hkv, D = 8, 8, 2, 128
     w = fi.workload("cfg2_llama8b_prefill")
     blocks = [fi.prefill_block(w, b, total=260) for b in range(M)]
-    schedules = {"shallow-half": [0, 1, 2, 3], "deep-half": [4, 5, 6, 7],
-                 "progressive": [0, 1, 3, 7], "regressive": [0, 4, 6, 7]}
+    from paper_2511_02647_amd.planning import sync_schedule
+    schedules = {name: sync_schedule(name, M, 4) for name in ("shallow-half", "deep-half", "progressive", "regressive")}
+    schedules["doubling intervals"] = [b in (0, 1, 3, 7) for b in range(M)]
     refs = {}
-    for name, sync_blocks in schedules.items():
+    for name, flags in schedules.items():
         for b in range(M):
-            sync = b in sync_blocks
+            sync = bool(flags[b])
             say("schedule %s block %d (%s)" % (name, b, "sync" if sync else "local"))
             got = prefill(*[x[:, :Hq if i == 0 else Hkv] for i, x in enumerate(blocks[b])], seg, Hq=Hq, Hkv=Hkv, D=D,
                           H=4, block=b, dtype=BF16, sync_override=int(sync))
