@@ -41,17 +41,21 @@ __device__ inline float sum_over_kgroups(float x) {
 }
 
 // COLSPLIT = false (at most 16 query columns, e.g. the G heads of one participant in a
-// local block): wavefront w takes tile rows 16w..16w+15; the 4 wavefronts are merged
-// through LDS at the end.  COLSPLIT = true (up to 64 query columns, sync blocks):
-// wavefront w takes query columns 16w..16w+15 against all 64 tile rows, so every
-// wavefront owns its output columns and nothing has to be merged.
+// local block): 4 wavefronts, wavefront w takes tile rows 16w..16w+15; they are merged
+// through LDS at the end.  COLSPLIT = true (up to 64 query columns, sync blocks): 8
+// wavefronts (two per SIMD, so that one's LDS and MFMA latencies hide behind the other);
+// wavefront w takes query columns 16 (w mod 4).. against tile rows 32 (w / 4)..+31.  Its two
+// 16-row sub-tiles fill the 8 k-slots per lane of one v_mfma_f32_16x16x32_bf16 in the second
+// product (slot e < 4: row 4 kg + e of the first sub-tile, e >= 4: of the second), which
+// halves its MFMA count.  The two row halves of a column block are merged through LDS.
 template <int D, bool COLSPLIT>
-__global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
-  using TL = KvTile<D, 0>;
+__global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(DecodeArgs a) {
+  constexpr int NW = COLSPLIT ? 8 : 4;
+  using TL = KvTile<D, 0, NW>;
   constexpr int KS = D / 32;                 // k-steps of S^T (16x16x32)
   constexpr int DT = D / 16;                 // 16-row tiles of O^T along head_dim
   constexpr int CPR = TL::CPR, ROWB = TL::ROWB, TILEB = TL::TILEB, IPW = TL::IPW;
-  constexpr int RSUB = COLSPLIT ? 4 : 1;     // 16-row sub-tiles a wavefront processes per tile
+  constexpr int RSUB = COLSPLIT ? 2 : 1;     // 16-row sub-tiles a wavefront processes per tile
   constexpr int QCOLS = COLSPLIT ? 64 : 16;  // query columns per workgroup
   constexpr int OPAD = D + 4;                // floats per row of the merge buffer
   // stage s: K tile at s*2*TILEB, V tile at s*2*TILEB + TILEB; after the stream the
@@ -72,7 +76,8 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
   const int G = Hq / Hkv;
   const int g = blockIdx.x % Hkv;
   const int gc = blockIdx.x / Hkv;  // chunk index over all segments
-  const int cb = blockIdx.y * QCOLS + (COLSPLIT ? 16 * wave : 0);  // first query column of this wavefront
+  const int rh = COLSPLIT ? wave >> 2 : 0;   // row half of the tile (column split only)
+  const int cb = blockIdx.y * QCOLS + (COLSPLIT ? 16 * (wave & 3) : 0);  // first query column of this wavefront
 
   // The segment tables sit in the kernel-argument buffer; a walk over them would take one
   // scalar-cache miss after another before the first cache row is requested.  Every lane
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
 #pragma unroll
     for (int rs = 0; rs < RSUB; ++rs) {
       s[rs] = f32x4{0.f, 0.f, 0.f, 0.f};
-      const int sub = (COLSPLIT ? rs : wave) * 16 * ROWB;
+      const int sub = (COLSPLIT ? 2 * rh + rs : wave) * 16 * ROWB;
 #pragma unroll
       for (int st = 0; st < KS; ++st) {
         const bf16x8 kf = __builtin_bit_cast(
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
     if (r_lo + kKvTile * (t + 1) > min_limit) {
 #pragma unroll
       for (int rs = 0; rs < RSUB; ++rs) {
-        const int row0 = r_lo + kKvTile * t + 16 * (COLSPLIT ? rs : wave) + 4 * kg;  // cache row of element 0
+        const int row0 = r_lo + kKvTile * t + 16 * (COLSPLIT ? 2 * rh + rs : wave) + 4 * kg;  // cache row of element 0
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           if (row0 + e >= limit) s[rs][e] = -INFINITY;
@@ -226,23 +231,58 @@ __global__ __launch_bounds__(256, 1) void decode_stream_kernel(DecodeArgs a) {
       pb[rs] = __builtin_bit_cast(s16x4, pv4);
     }
 
-    // ---- O^T[d][q] += V^T P^T: k-slot 4 kg + e of the 16x16x16 MFMA = sub-tile row 4 kg + e -----
+    // ---- O^T[d][q] += V^T P^T -----------------------------------------------------------------
+    if constexpr (COLSPLIT) {
+      // both sub-tiles in one 16x16x32 MFMA: k-slot 8 kg + e = row 4 kg + (e mod 4) of sub-tile e / 4
+      const int sub = 2 * rh * 16 * ROWB;
+      const s16x8 pp = __builtin_shufflevector(pb[0], pb[1], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-    for (int rs = 0; rs < RSUB; ++rs) {
-      const int sub = (COLSPLIT ? rs : wave) * 16 * ROWB;
+      for (int dt = 0; dt < DT; ++dt) {
+        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(lds0 + (kb + TILEB + sub + v_off[dt])));
+        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(lds0 + (kb + TILEB + sub + 16 * ROWB + v_off[dt])));
+        const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pp),
+                                                        o[dt], 0, 0, 0);
+      }
+    } else {
+      // k-slot 4 kg + e of the 16x16x16 MFMA = sub-tile row 4 kg + e
+      const int sub = wave * 16 * ROWB;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         const s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
             (__attribute__((address_space(3))) s16x4*)(lds0 + (kb + TILEB + sub + v_off[dt])));
-        o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pb[rs], o[dt], 0, 0, 0);
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pb[0], o[dt], 0, 0, 0);
       }
     }
   }
 
   l_run = sum_over_kgroups(l_run);
   if constexpr (COLSPLIT) {
-    // every wavefront owns its 16 columns: write the partial straight from registers
-    if (col_ok) {
+    // ---- merge the two row halves of a column block: half 1 hands (m, l, O) to half 0 -------
+    __syncthreads();  // every wavefront is done with the tile ring
+    f32x4* xo = reinterpret_cast<f32x4*>(smem) + (wave & 3) * (DT * 64) + lane;         // [DT][64 lanes]
+    float* xml = reinterpret_cast<float*>(smem + 4 * DT * 64 * 16) + (wave & 3) * 128 + lane;  // m, l per lane
+    if (rh == 1) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) xo[dt * 64] = o[dt];
+      xml[0] = m_run;
+      xml[64] = l_run;
+    }
+    __syncthreads();
+    if (rh == 0) {
+      const float m1 = xml[0], l1 = xml[64];
+      const float mm = fmaxf(m_run, m1);
+      const float mu = (mm == -INFINITY) ? 0.f : mm;
+      const float f0 = __builtin_amdgcn_exp2f(m_run - mu), f1 = __builtin_amdgcn_exp2f(m1 - mu);
+      m_run = mm;
+      l_run = l_run * f0 + l1 * f1;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * f0 + xo[dt * 64] * f1;
+    }
+    // half 0 owns the merged 16 columns: write the partial straight from registers
+    if (rh == 0 && col_ok) {
       const int64_t prow = ((int64_t)g * a.n_chunks + gc) * a.cols + col;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(a.part_o + prow * D + 16 * dt + 4 * kg) = o[dt];
@@ -378,11 +418,18 @@ __global__ void decode_zero_counters_kernel(int32_t* counters, int n) {
   if (i < n) counters[i] = 0;
 }
 
-// Merges the chunk partials of one (participant, query head) and writes the output row.
+// Merges the chunk partials of one (participant, query head) and writes the output row:
+//   o = sum_c O_c 2^(m_c - m) / sum_c l_c 2^(m_c - m),  m = max_c m_c.
+// D/4 x 4 threads: thread (cg, d4) sums 4 head-dim elements over the chunks c = cg (mod 4),
+// all its loads in flight at once (the kernel is a chain of memory round trips: (m, l) of
+// every chunk, then the partial O rows, then the store); the 4 chunk groups meet in LDS.
 template <typename T>
 __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
+  constexpr int CG = 4;
+  __shared__ float m_s[256];
   __shared__ float w_s[256];
-  __shared__ float red_s[8];
+  __shared__ float l_s[256];
+  __shared__ f32x4 acc_s[CG][64];
   const int n = blockIdx.x / a.Hq;
   const int h = blockIdx.x % a.Hq;
   const int G = a.Hq / a.Hkv;
@@ -392,47 +439,51 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
   const int col = a.is_sync ? n * G + hh : hh;
   const int64_t base = (int64_t)g * a.n_chunks;
   const int tid = threadIdx.x;
-  const int D = a.D;
+  const int D = a.D, D4 = D / 4;
+  const int d4 = tid % D4, cg = tid / D4;  // blockDim = D4 * CG
+  const int64_t cstride = a.cols;          // partial rows between consecutive chunks
 
-  // row maximum over the chunks
+  // row maximum over all chunks
   float mm = -INFINITY;
-  for (int cc = c0 + tid; cc < c1; cc += blockDim.x) mm = fmaxf(mm, a.part_ml[((base + cc) * a.cols + col) * 2]);
+  for (int cc = c0 + tid; cc < c1; cc += blockDim.x) mm = fmaxf(mm, a.part_ml[((base + cc) * cstride + col) * 2]);
   mm = wave_max(mm);
-  if ((tid & 63) == 0) red_s[tid >> 6] = mm;
+  if ((tid & 63) == 0) m_s[tid >> 6] = mm;
   __syncthreads();
   mm = -INFINITY;
-  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) mm = fmaxf(mm, red_s[w]);
+  for (int w = 0; w < (int)((blockDim.x + 63) >> 6); ++w) mm = fmaxf(mm, m_s[w]);
   const float mu = (mm == -INFINITY) ? 0.f : mm;
 
-  float acc = 0.f, den = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float den = 0.f;
   for (int cb = c0; cb < c1; cb += 256) {
     const int nb = min(256, c1 - cb);
     __syncthreads();
-    for (int i = tid; i < nb; i += blockDim.x)
-      w_s[i] = __builtin_amdgcn_exp2f(a.part_ml[((base + cb + i) * a.cols + col) * 2] - mu);
-    __syncthreads();
-    if (tid < D) {
-      int i = 0;
-      for (; i + 4 <= nb; i += 4) {
-        const float* p0 = a.part_o + ((base + cb + i) * a.cols + col) * D + tid;
-        const int64_t st = (int64_t)a.cols * D;
-        const float x0 = p0[0], x1 = p0[st], x2 = p0[2 * st], x3 = p0[3 * st];
-        acc = fmaf(x0, w_s[i], acc);
-        acc = fmaf(x1, w_s[i + 1], acc);
-        acc = fmaf(x2, w_s[i + 2], acc);
-        acc = fmaf(x3, w_s[i + 3], acc);
-      }
-      for (; i < nb; ++i) acc = fmaf(a.part_o[((base + cb + i) * a.cols + col) * D + tid], w_s[i], acc);
+    for (int i = tid; i < nb; i += blockDim.x) {
+      const float* ml = a.part_ml + ((base + cb + i) * cstride + col) * 2;
+      w_s[i] = __builtin_amdgcn_exp2f(ml[0] - mu);
+      l_s[i] = ml[1];
     }
-    for (int i = 0; i < nb; ++i) den = fmaf(a.part_ml[((base + cb + i) * a.cols + col) * 2 + 1], w_s[i], den);
+    __syncthreads();
+    const float* po = a.part_o + ((base + cb) * cstride + col) * D + 4 * d4;
+#pragma unroll 8
+    for (int i = cg; i < nb; i += CG) acc += *reinterpret_cast<const f32x4*>(po + i * cstride * D) * w_s[i];
+    if (tid == 0)
+      for (int i = 0; i < nb; ++i) den = fmaf(l_s[i], w_s[i], den);
   }
-  if (tid < D) {
-    const float val = den > 0.f ? acc / den : 0.f;
-    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * D + tid;
-    if constexpr (sizeof(T) == 2)
-      *out = f32_to_bf16_bits(val);
-    else
-      *out = val;
+  acc_s[cg][d4] = acc;
+  if (tid == 0) m_s[8] = den;
+  __syncthreads();
+  if (cg == 0) {
+    const float dn = m_s[8];
+    const f32x4 sum = (acc_s[0][d4] + acc_s[1][d4]) + (acc_s[2][d4] + acc_s[3][d4]);
+    const f32x4 val = sum * (dn > 0.f ? 1.f / dn : 0.f);
+    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * D + 4 * d4;
+    if constexpr (sizeof(T) == 2) {
+      const bf16x4 w4 = {(bf16_t)val[0], (bf16_t)val[1], (bf16_t)val[2], (bf16_t)val[3]};
+      *reinterpret_cast<u32x2*>(out) = __builtin_bit_cast(u32x2, w4);
+    } else {
+      *reinterpret_cast<f32x4*>(out) = val;
+    }
   }
 }
 
@@ -523,7 +574,7 @@ hipError_t launch_stream_mode(const DecodeArgs& a, hipStream_t s) {
   }
   const int qcols = COLSPLIT ? 64 : 16;
   dim3 grid((unsigned)(a.n_chunks * a.Hkv), (unsigned)((a.cols + qcols - 1) / qcols), 1);
-  hipLaunchKernelGGL((decode_stream_kernel<D, COLSPLIT>), grid, dim3(256), decode_smem_bytes<D>(), s, a);
+  hipLaunchKernelGGL((decode_stream_kernel<D, COLSPLIT>), grid, dim3(COLSPLIT ? 512 : 256), decode_smem_bytes<D>(), s, a);
   return hipGetLastError();
 }
 
@@ -550,7 +601,7 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   if (a.fuse_combine) return hipSuccess;
-  hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq)), dim3(a.D <= 64 ? 64 : 128), 0,
+  hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq)), dim3(a.D), 0,
                      s, a);
   return hipGetLastError();
 }

@@ -17,6 +17,7 @@ namespace fedattn {
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
 
@@ -75,7 +76,8 @@ __device__ inline float sum_across_halves(float x) {
 // VSWZ selects the chunk swizzle of V tiles: the transposing reads of the 32x32x16
 // product touch 4 rows x 4 chunks per 32 lanes (VSWZ = 1: f = 4 (row mod 4)), those of the
 // 16x16x16 product 8 rows x 2 chunks (VSWZ = 0: f = 2 (row mod 8)).
-template <int D, int VSWZ>
+// NW = wavefronts that load a tile together (4, or 8 for 8-wave workgroups sharing one tile).
+template <int D, int VSWZ, int NW = 4>
 struct KvTile {
   static constexpr int KSTEPS = D / 16;         // MFMA k-steps of S^T = K Q^T
   static constexpr int DT = D / 32;             // 32-row tiles of O^T along head_dim
@@ -83,7 +85,8 @@ struct KvTile {
   static constexpr int ROWB = D * 2;            // LDS bytes per K/V row (unpadded; chunks XOR-swizzled)
   static constexpr int TILEB = kKvTile * ROWB;  // one K or V stage
   static constexpr int NINST = TILEB / 1024;    // direct-to-LDS load instructions per tile (1 KB each)
-  static constexpr int IPW = NINST / 4;         // per wavefront (4 wavefronts load a tile together)
+  static constexpr int IPW = NINST / NW;        // per wavefront
+  static_assert(NINST % NW == 0, "tile loads must divide evenly among the wavefronts");
 
   // HBM -> LDS: one load instruction moves 64 x 16 bytes to 1 KB of consecutive LDS
   // (lane l lands at +16 l).  LDS slot (row, cp) receives chunk cp ^ f(row) of the row:
