@@ -265,20 +265,29 @@ __device__ __attribute__((always_inline)) inline float softmax_max(const f32x16 
 }
 
 // Part 2: exponentials; adds this lane's share of the row sum to l_run and leaves P^T
-// in bf16 in pb.
+// in bf16 in pb.  The row sum is taken over the bf16 weights, the ones the second product
+// uses (numerator and denominator of the softmax then carry the same rounding), two at a
+// time with v_dot2c_f32_bf16 against (1, 1): half the additions of a sum over fp32 weights.
 __device__ __attribute__((always_inline)) inline void softmax_exp(const f32x16 (&s)[2], float sc, float m_use,
                                                                    float& l_run, bf16x8 (&pb)[4]) {
+  const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
   float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
   for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-    for (int e = 0; e < 16; e += 2) {
+    for (int e = 0; e < 16; e += 4) {
       const float p0 = __builtin_amdgcn_exp2f(fmaf(s[aa][e], sc, -m_use));
       const float p1 = __builtin_amdgcn_exp2f(fmaf(s[aa][e + 1], sc, -m_use));
-      ps0 += p0;
-      ps1 += p1;
-      pb[aa * 2 + (e >> 3)][e & 7] = (bf16_t)p0;
-      pb[aa * 2 + (e >> 3)][(e & 7) + 1] = (bf16_t)p1;
+      const float p2 = __builtin_amdgcn_exp2f(fmaf(s[aa][e + 2], sc, -m_use));
+      const float p3 = __builtin_amdgcn_exp2f(fmaf(s[aa][e + 3], sc, -m_use));
+      const bf16x2 q0 = {(bf16_t)p0, (bf16_t)p1};
+      const bf16x2 q1 = {(bf16_t)p2, (bf16_t)p3};
+      ps0 = __builtin_amdgcn_fdot2_f32_bf16(q0, ones, ps0, false);
+      ps1 = __builtin_amdgcn_fdot2_f32_bf16(q1, ones, ps1, false);
+      pb[aa * 2 + (e >> 3)][e & 7] = q0[0];
+      pb[aa * 2 + (e >> 3)][(e & 7) + 1] = q0[1];
+      pb[aa * 2 + (e >> 3)][(e & 7) + 2] = q1[0];
+      pb[aa * 2 + (e >> 3)][(e & 7) + 3] = q1[1];
     }
   l_run += ps0 + ps1;
 }
