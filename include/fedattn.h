@@ -96,8 +96,10 @@ size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t
  *                  seg_offsets[n] + c*chunk_tokens ... (clipped to the segment);
  *                  flags are stored participant after participant.  Read only in
  *                  sync blocks.  chunk_tokens must be positive when keep_chunks is
- *                  given (1 = token-granular exchange); multiples of 64 keep
- *                  bf16 on the MFMA kernel, other sizes run the general kernel.
+ *                  given (1 = token-granular exchange).  On the MFMA path (bf16,
+ *                  D = 64 or 128) chunks that are multiples of 64 are visited where
+ *                  they are; finer chunks have their kept rows packed into the
+ *                  workspace first (a K,V-sized copy).  One block per call.
  *   sync_override  -1: rule above; 0: force local; 1: force sync (variable sync
  *                  schedules H_t).
  *   workspace      device, >= fedattn_workspace_bytes(PREFILL); may be NULL when

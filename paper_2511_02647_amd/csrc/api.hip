@@ -53,12 +53,12 @@ fedattn_status check_offsets(const fedattn_params* p, const int32_t* seg) {
   return FEDATTN_OK;
 }
 
-bool use_mfma_prefill(const fedattn_params* p, bool has_keep, int chunk_tokens) {
-  if (p->dtype != FEDATTN_BF16) return false;
-  if (p->head_dim != 64 && p->head_dim != 128) return false;
-  if (has_keep && chunk_tokens % kKvTile != 0) return false;
-  return true;
+bool use_mfma_prefill(const fedattn_params* p) {
+  return p->dtype == FEDATTN_BF16 && (p->head_dim == 64 || p->head_dim == 128);
 }
+
+// keep chunks that are not whole 64-row tiles: the MFMA path packs the kept rows first
+bool needs_row_packing(int chunk_tokens) { return chunk_tokens > 0 && chunk_tokens % kKvTile != 0; }
 
 int env_int(const char* name, int dflt) {
   const char* s = getenv(name);
@@ -100,10 +100,27 @@ int decode_chunk_rows(int64_t total_rows, int Hkv) {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // prefill workspace: [kept_cum: (kMaxP+1) int32, padded][kept_tiles: int2 per 64-row tile]
+// and, for keep chunks finer than a tile on the MFMA path:
+// [kept_rows: kMaxP int32][src_index: int32 per token][packed K][packed V]
 constexpr size_t kKeptCumBytes = 1024;
-size_t prefill_ws_bytes(const fedattn_params* p, int32_t tokens) {
+constexpr size_t kKeptRowsBytes = 512;
+struct PrefillWs {
+  size_t tiles_off, rows_off, index_off, k_off, v_off, total;
+};
+PrefillWs prefill_ws_layout(const fedattn_params* p, int32_t tokens, int32_t chunk_tokens) {
+  PrefillWs w;
   const size_t max_tiles = (size_t)tokens / kKvTile + (size_t)p->n_participants + 1;
-  return kKeptCumBytes + align_up(max_tiles * sizeof(int2), 16);
+  w.tiles_off = kKeptCumBytes;
+  w.rows_off = w.tiles_off + align_up(max_tiles * sizeof(int2), 256);
+  w.index_off = w.k_off = w.v_off = w.total = w.rows_off;
+  if (use_mfma_prefill(p) && needs_row_packing(chunk_tokens)) {
+    const size_t kv_bytes = (size_t)tokens * (size_t)p->n_kv_heads * (size_t)p->head_dim * 2;
+    w.index_off = w.rows_off + kKeptRowsBytes;
+    w.k_off = w.index_off + align_up((size_t)tokens * 4, 256);
+    w.v_off = w.k_off + align_up(kv_bytes, 256);
+    w.total = w.v_off + align_up(kv_bytes, 256);
+  }
+  return w;
 }
 
 // chunk counters of the fused combine, one per (KV head, participant), at the end of the workspace
@@ -160,7 +177,9 @@ fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t 
   a.scale = resolve_scale(p);
   a.seg.n = N;
 
-  const bool mfma = use_mfma_prefill(p, has_keep, chunk_tokens);
+  const bool mfma = use_mfma_prefill(p);
+  a.k_list = k;
+  a.v_list = v;
   const int G = a.Hq / a.Hkv;
   a.heads_per_wg = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
   a.q_tile_rows = kWaveRows * (4 / a.heads_per_wg);
@@ -191,16 +210,27 @@ fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t 
 
   if (mfma) {
     if (a.keep_chunks) {
-      const size_t need = prefill_ws_bytes(p, total);
-      if (!workspace || workspace_bytes < need)
-        return fail(FEDATTN_EWORKSPACE, "prefill with a keep-list needs %zu workspace bytes, got %zu", need,
+      if (n_blocks != 1) return fail(FEDATTN_EUNSUPPORTED, "a keep-list applies to one block per call");
+      const PrefillWs w = prefill_ws_layout(p, total, chunk_tokens);
+      if (!workspace || workspace_bytes < w.total)
+        return fail(FEDATTN_EWORKSPACE, "prefill with a keep-list needs %zu workspace bytes, got %zu", w.total,
                     workspace_bytes);
       if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
-      int32_t* kept_cum = reinterpret_cast<int32_t*>(workspace);
-      int2* kept_tiles = reinterpret_cast<int2*>(reinterpret_cast<unsigned char*>(workspace) + kKeptCumBytes);
+      unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+      int32_t* kept_cum = reinterpret_cast<int32_t*>(ws);
+      int2* kept_tiles = reinterpret_cast<int2*>(ws + w.tiles_off);
       a.kept_cum = kept_cum;
       a.kept_tiles = kept_tiles;
-      hipError_t e = launch_build_kept_tiles(a, kept_tiles, kept_cum, s);
+      hipError_t e;
+      if (needs_row_packing(chunk_tokens)) {
+        a.k_list = ws + w.k_off;
+        a.v_list = ws + w.v_off;
+        e = launch_pack_kept_rows(a, reinterpret_cast<int32_t*>(ws + w.rows_off),
+                                  reinterpret_cast<int32_t*>(ws + w.index_off), ws + w.k_off, ws + w.v_off,
+                                  kept_tiles, kept_cum, s);
+      } else {
+        e = launch_build_kept_tiles(a, kept_tiles, kept_cum, s);
+      }
       if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "keep-list compaction: %s", hipGetErrorString(e));
     }
     hipError_t e = launch_prefill_mfma(a, n_blocks, s);
@@ -222,7 +252,7 @@ int fedattn_is_sync_block(int32_t sync_interval, int32_t block_idx) {
 
 size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t tokens, int32_t chunk_tokens) {
   if (check_params(params) != FEDATTN_OK || tokens < 0) return 0;
-  if (op == FEDATTN_OP_PREFILL) return chunk_tokens > 0 ? prefill_ws_bytes(params, tokens) : 0;
+  if (op == FEDATTN_OP_PREFILL) return chunk_tokens > 0 ? prefill_ws_layout(params, tokens, chunk_tokens).total : 0;
   if (op == FEDATTN_OP_DECODE) return decode_ws_bytes(params, tokens);
   fail(FEDATTN_EINVAL, "unknown op %d", op);
   return 0;

@@ -31,7 +31,9 @@ struct PrefillArgs {
   int64_t q_block_stride;   // elements between consecutive blocks (batched launch)
   int64_t kv_block_stride;
   const uint8_t* keep_chunks;   // device, or nullptr
-  const int2* kept_tiles;       // device (workspace): (first token, valid rows) of kept 64-row tiles
+  const void* k_list;           // K, V the kept-tile list refers to: k, v themselves when the keep chunks
+  const void* v_list;           // are whole tiles, else the packed copies of the kept rows (workspace)
+  const int2* kept_tiles;       // device (workspace): (first row, valid rows) of kept 64-row tiles
   const int32_t* kept_cum;      // device (workspace): kept tiles of participants < n, [N+1]
   int32_t chunk_tokens;
   int32_t total;
@@ -85,6 +87,8 @@ hipError_t launch_prefill_generic(const PrefillArgs& a, int n_blocks, int dtype,
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s);
 hipError_t launch_build_kept_tiles(const PrefillArgs& a, int2* kept_tiles, int32_t* kept_cum,
                                    hipStream_t s);
+hipError_t launch_pack_kept_rows(const PrefillArgs& a, int32_t* kept_rows, int32_t* src_index, void* k_packed,
+                                 void* v_packed, int2* kept_tiles, int32_t* kept_cum, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_zero_counters(int32_t* counters, int n, hipStream_t s);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t s);

@@ -129,6 +129,8 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + (int64_t)block * a.q_block_stride;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(a.k) + (int64_t)block * a.kv_block_stride + g * D;
   const uint16_t* vp = reinterpret_cast<const uint16_t*>(a.v) + (int64_t)block * a.kv_block_stride + g * D;
+  const uint16_t* kp_list = reinterpret_cast<const uint16_t*>(a.k_list) + g * D;  // kept-tile list (one block)
+  const uint16_t* vp_list = reinterpret_cast<const uint16_t*>(a.v_list) + g * D;
   uint16_t* op = reinterpret_cast<uint16_t*>(a.out) + (int64_t)block * a.q_block_stride;
   const float sc = a.scale * kLog2e;
   const int row_elems = Hkv * D;  // elements between consecutive KV rows in HBM
@@ -182,8 +184,9 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     int kv0, len;
     bool ct;
     tile_desc(w, it, kv0, len, ct);
-    tile_io.template dma<false>(kp + (int64_t)kv0 * row_elems, lds_base + st, len);
-    tile_io.template dma<true>(vp + (int64_t)kv0 * row_elems, lds_base + 2 * TILEB + st, len);
+    const bool listed = it < w.n_list;
+    tile_io.template dma<false>((listed ? kp_list : kp) + (int64_t)kv0 * row_elems, lds_base + st, len);
+    tile_io.template dma<true>((listed ? vp_list : vp) + (int64_t)kv0 * row_elems, lds_base + 2 * TILEB + st, len);
   };
   const int head = g * G + hsub * HS + (wave % HS);
   // Q fragments (B operand of S^T): lane (q row = l32, half hf) holds
@@ -393,7 +396,100 @@ __global__ __launch_bounds__(kMaxP) void build_kept_tiles_kernel(PrefillArgs a, 
   }
 }
 
+// ---- keep-lists finer than a tile: the kept rows of every participant are packed ------------
+// A sync block under sparse KV exchange sees, of a remote participant, only the rows the
+// keep-list flags.  When a flag covers whole 64-row tiles the attention kernel visits the kept
+// tiles where they are; for finer lists (down to single tokens) three small kernels first
+// gather each participant's kept rows into the front of its own segment of a packed K, V copy,
+// so that the attention kernel still walks dense tiles.  Among remote rows only membership
+// matters (a remote participant lies entirely before or entirely after the query in the
+// global order), so packing loses nothing.
+
+// Workgroup m scans participant m's flags: src_index[lo + p] = global row of its p-th kept
+// row (-1 past the last), kept_rows[m] = their number.
+__global__ __launch_bounds__(256) void scan_kept_rows_kernel(PrefillArgs a, int32_t* kept_rows, int32_t* src_index) {
+  __shared__ int wave_cnt[4];
+  const int m = blockIdx.x;
+  const int lo = a.seg.seg_off[m], hi = a.seg.seg_off[m + 1];
+  const uint8_t* keep = a.keep_chunks + a.seg.chunk_cum[m];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int carry = 0;
+  for (int base = lo; base < hi; base += 256) {
+    const int t = base + tid;
+    const bool flag = t < hi && keep[(t - lo) / a.chunk_tokens] != 0;
+    const unsigned long long bal = __builtin_amdgcn_ballot_w64(flag);
+    const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+    __syncthreads();  // wave_cnt of the previous round has been read
+    if (lane == 0) wave_cnt[wave] = __builtin_popcountll(bal);
+    __syncthreads();
+    int pos = carry + before;
+    for (int w = 0; w < wave; ++w) pos += wave_cnt[w];
+    if (flag) src_index[lo + pos] = t;
+    carry += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+  }
+  for (int p = lo + carry + tid; p < hi; p += 256) src_index[p] = -1;
+  if (tid == 0) kept_rows[m] = carry;
+}
+
+// The packed rows of participant m occupy [seg_off[m], seg_off[m] + kept_rows[m]): the list
+// of their 64-row tiles (the last one ragged) and the tile count before each participant.
+__global__ __launch_bounds__(kMaxP) void build_packed_tiles_kernel(PrefillArgs a, const int32_t* kept_rows,
+                                                                   int2* kept_tiles, int32_t* kept_cum) {
+  __shared__ int cnt[kMaxP + 1];
+  const int n = threadIdx.x;
+  const int N = a.seg.n;
+  const int kc = n < N ? kept_rows[n] : 0;
+  cnt[n] = (kc + kKvTile - 1) / kKvTile;
+  __syncthreads();
+  if (n == 0) {
+    int run = 0;
+    for (int i = 0; i < N; ++i) {
+      const int c = cnt[i];
+      cnt[i] = run;
+      kept_cum[i] = run;
+      run += c;
+    }
+    kept_cum[N] = run;
+  }
+  __syncthreads();
+  if (n < N) {
+    const int lo = a.seg.seg_off[n];
+    int w = cnt[n];
+    for (int t = 0; t < kc; t += kKvTile) kept_tiles[w++] = make_int2(lo + t, min(kKvTile, kc - t));
+  }
+}
+
+// Packed row p of K and V = row src_index[p] of the block's K and V (16 bytes per thread).
+__global__ __launch_bounds__(256) void gather_kept_rows_kernel(PrefillArgs a, const int32_t* src_index,
+                                                               uint4* k_packed, uint4* v_packed) {
+  const int row_vecs = a.Hkv * a.D / 8;  // 16-byte pieces per bf16 row
+  const int rows_per_wg = max(1, 256 / row_vecs);
+  const uint4* src = reinterpret_cast<const uint4*>(blockIdx.y == 0 ? a.k : a.v);
+  uint4* dst = blockIdx.y == 0 ? k_packed : v_packed;
+  for (int i = threadIdx.x; i < rows_per_wg * row_vecs; i += 256) {
+    const int p = blockIdx.x * rows_per_wg + i / row_vecs;
+    if (p >= a.total) break;
+    const int from = src_index[p];
+    if (from >= 0) dst[(int64_t)p * row_vecs + i % row_vecs] = src[(int64_t)from * row_vecs + i % row_vecs];
+  }
+}
+
 }  // namespace
+
+hipError_t launch_pack_kept_rows(const PrefillArgs& a, int32_t* kept_rows, int32_t* src_index, void* k_packed,
+                                 void* v_packed, int2* kept_tiles, int32_t* kept_cum, hipStream_t s) {
+  hipLaunchKernelGGL(scan_kept_rows_kernel, dim3((unsigned)a.seg.n), dim3(256), 0, s, a, kept_rows, src_index);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(build_packed_tiles_kernel, dim3(1), dim3(kMaxP), 0, s, a, kept_rows, kept_tiles, kept_cum);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int row_vecs = a.Hkv * a.D / 8;
+  const int rows_per_wg = row_vecs >= 256 ? 1 : 256 / row_vecs;
+  hipLaunchKernelGGL(gather_kept_rows_kernel, dim3((unsigned)((a.total + rows_per_wg - 1) / rows_per_wg), 2), dim3(256),
+                     0, s, a, src_index, reinterpret_cast<uint4*>(k_packed), reinterpret_cast<uint4*>(v_packed));
+  return hipGetLastError();
+}
 
 template <int D, int NG>
 hipError_t launch_prefill_mfma_t(const PrefillArgs& a, dim3 grid, hipStream_t s) {

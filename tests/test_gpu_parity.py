@@ -111,6 +111,30 @@ def test_mfma_prefill_sparse_exchange(chunk):
     check(got, oracle.attend_block(q, k, v, seg, is_sync=False), BF16, "local block with keep-list")
 
 
+@pytest.mark.parametrize("chunk", [1, 16, 100])
+def test_mfma_prefill_keep_lists_finer_than_a_tile(chunk):
+    """Keep chunks that are not whole 64-row tiles (down to single tokens): the MFMA path packs
+    every participant's kept rows and walks dense tiles of the packed copy."""
+    seg = np.array([0, 200, 500, 731, 731, 1000], dtype=np.int32)   # an empty participant, ragged tails
+    Hq, Hkv, D = 8, 2, 128
+    q, k, v = rand_block(41, 1000, Hq, Hkv, D)
+    counts = fi.chunk_counts(np.diff(seg), chunk)
+    nch, first = int(counts.sum()), np.concatenate([[0], np.cumsum(counts)])
+    g = np.random.default_rng(6 + chunk)
+    random_flags = (g.random(nch) < 0.3).astype(np.uint8)
+    mixed = random_flags.copy()
+    mixed[first[1]:first[2]] = 0      # participant 1 shares nothing
+    mixed[first[2]:first[3]] = 1      # participant 2 shares everything
+    for name, flags in [("random", random_flags), ("none/all mix", mixed), ("all", np.ones(nch, np.uint8))]:
+        kt = oracle.expand_keep_chunks(flags, seg, chunk)
+        for causal in (True, False):
+            say("mfma packed keep-list chunk=%d keep=%s causal=%d" % (chunk, name, causal))
+            got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, causal=causal,
+                          keep_chunks=flags, chunk_tokens=chunk)
+            ref = oracle.attend_block(q, k, v, seg, is_sync=True, causal=causal, keep_tok=kt)
+            check(got, ref, BF16, "packed keep-list chunk=%d keep=%s causal=%d" % (chunk, name, causal))
+
+
 def test_prefill_blocks_batched_equals_per_block():
     w = fi.workload("cfg2_llama8b_prefill")
     seg = np.array([0, 130, 200, 333], dtype=np.int32)
@@ -167,7 +191,7 @@ def test_participant_exclusion_and_token_granular_exchange():
     say("participant 1 excluded from the aggregation")
     got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, keep_chunks=flags, chunk_tokens=64)
     check(got, oracle.attend_block(q, k, v, seg, is_sync=True, keep_tok=kt), BF16, "participant excluded")
-    # token-granular random exchange (chunk = 1 token, general kernel)
+    # token-granular random exchange (chunk = 1 token: kept rows packed, MFMA kernel)
     tok = (np.random.default_rng(5).random(448) < 0.3).astype(np.uint8)
     say("token-granular sparse exchange")
     got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, keep_chunks=tok, chunk_tokens=1)
