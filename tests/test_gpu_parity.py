@@ -76,6 +76,47 @@ def test_mfma_prefill_small_full(Hq, Hkv, D):
             check(got, ref, BF16, "mfma Hq=%d Hkv=%d D=%d causal=%d sync=%d" % (Hq, Hkv, D, causal, sync))
 
 
+@pytest.mark.parametrize("N", [65, 100, 128])
+def test_many_participants(N):
+    """More than 64 participants (up to the maximum of 128): the kernels look their segment up in
+    tables that span two registers per lane."""
+    g = np.random.default_rng(100 + N)
+    lens = g.integers(0, 40, size=N)
+    lens[g.integers(0, N, size=5)] = 0            # some empty participants
+    lens[N - 1] = 70                              # the last one spans two KV tiles
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(seg[-1])
+    Hq, Hkv, D = 8, 2, 128
+    q, k, v = rand_block(50 + N, total, Hq, Hkv, D)
+    for sync in (0, 1):
+        say("prefill N=%d sync=%d" % (N, sync))
+        got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, sync_override=sync)
+        check(got, oracle.attend_block(q, k, v, seg, is_sync=bool(sync)), BF16, "prefill N=%d sync=%d" % (N, sync))
+    # sparse exchange, token-granular (packed rows) and whole participants dropped
+    flags = (g.random(total) < 0.5).astype(np.uint8)
+    flags[seg[N // 2]:seg[N // 2 + 10]] = 0
+    say("prefill N=%d sparse" % N)
+    got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, keep_chunks=flags, chunk_tokens=1)
+    check(got, oracle.attend_block(q, k, v, seg, is_sync=True, keep_tok=flags), BF16, "prefill N=%d sparse" % N)
+    # decode over caches of the same layout (capacity = the segments, every row valid but a few)
+    cache_lens = np.maximum(lens - g.integers(0, 3, size=N), 0).astype(np.int32)
+    cache_lens[N - 1] = 70
+    qd, _, _ = rand_block(60 + N, N, Hq, Hkv, D)
+    for sync in (0, 1):
+        say("decode N=%d sync=%d" % (N, sync))
+        got = decode(qd, k, v, seg, cache_lens, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, sync_override=sync)
+        ref = oracle.decode_step(qd, k, v, seg, cache_lens, is_sync=bool(sync))
+        check(got, ref, BF16, "decode N=%d sync=%d" % (N, sync))
+    # every participant has rows: local blocks merge their chunks inside the streaming kernel
+    cache_lens = np.maximum(lens, 1).astype(np.int32)
+    cap = np.maximum(lens, 1)
+    seg2 = np.concatenate([[0], np.cumsum(cap)]).astype(np.int32)
+    _, k2, v2 = rand_block(70 + N, int(seg2[-1]), Hq, Hkv, D)
+    say("decode N=%d local, no empty cache" % N)
+    got = decode(qd, k2, v2, seg2, cache_lens, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, sync_override=0)
+    check(got, oracle.decode_step(qd, k2, v2, seg2, cache_lens, is_sync=False), BF16, "decode N=%d local fused" % N)
+
+
 def test_mfma_prefill_sync_rule_and_scale():
     seg = np.array([0, 96, 224], dtype=np.int32)
     q, k, v = rand_block(8, 224, 4, 1, 128)
