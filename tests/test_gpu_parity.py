@@ -312,6 +312,55 @@ def test_cfg5_sparse_sync_full_size():
                        what="cfg5 block %d" % b, salt=20 + b)
 
 
+def test_offsets_beyond_32_bits():
+    """One million tokens, 128 participants: byte offsets into q, k, v, out and the caches pass
+    2^32 (q/out 8.6 GB, k/v 4.3 GB each).  Inputs of this size are drawn on the device; the
+    oracle gets host copies of the segments and heads it checks."""
+    N, seglen, Hq, Hkv, D = 128, 8192, 32, 16, 128
+    total = N * seglen
+    seg = (np.arange(N + 1) * seglen).astype(np.int32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    q = torch.randn(total, Hq, D, generator=g, device="cuda", dtype=BF16)
+    k = torch.randn(total, Hkv, D, generator=g, device="cuda", dtype=BF16)
+    v = torch.randn(total, Hkv, D, generator=g, device="cuda", dtype=BF16)
+    out = torch.full_like(q, float("nan"))
+    p = fa.make_params(N, Hq, Hkv, D, 0, BF16)
+    say("prefill local, 2^20 tokens")
+    fa.fedattn_prefill(p, 0, q, k, v, out, seg, sync_override=0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    for n in (0, 63, 127):
+        sl = slice(int(seg[n]), int(seg[n + 1]))
+        rows = np.concatenate([[0, 1, 63, 64, seglen - 2, seglen - 1], rng.integers(0, seglen, size=26)]).astype(np.int32)
+        heads = rng.integers(0, Hq, size=rows.shape[0]).astype(np.int32)
+        ref = oracle.attend_rows(host(q[sl]), host(k[sl]), host(v[sl]), [0, seglen], rows, heads, is_sync=False)
+        check(host(out[sl])[rows, heads], ref, BF16, "2^20 tokens, local block, participant %d" % n)
+    del out
+
+    # decode over the same buffers as caches
+    lens = rng.integers(seglen - 200, seglen, size=N, endpoint=True).astype(np.int32)
+    qd = torch.randn(N, Hq, D, generator=g, device="cuda", dtype=BF16)
+    od = torch.full_like(qd, float("nan"))
+    ws = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, total), dtype=torch.uint8, device="cuda")
+    say("decode local, caches of 2^20 rows")
+    fa.fedattn_decode(p, 0, qd, k, v, od, seg, lens, sync_override=0, workspace=ws)
+    torch.cuda.synchronize()
+    for n in (0, 127):
+        sl = slice(int(seg[n]), int(seg[n + 1]))
+        ref = oracle.decode_step(host(qd[n:n + 1]), host(k[sl]), host(v[sl]), [0, seglen], lens[n:n + 1], is_sync=False)
+        check(host(od[n:n + 1]), ref, BF16, "2^20 cache rows, local decode, participant %d" % n)
+    say("decode sync, caches of 2^20 rows")
+    od.fill_(float("nan"))
+    fa.fedattn_decode(p, 0, qd, k, v, od, seg, lens, sync_override=1, workspace=ws)
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    for h in (0, Hq - 1):
+        kv = h // G
+        ref = oracle.decode_step(host(qd[:, h:h + 1]), host(k[:, kv:kv + 1]), host(v[:, kv:kv + 1]), seg, lens, is_sync=True)
+        check(host(od[:, h:h + 1]), ref, BF16, "2^20 cache rows, sync decode, head %d" % h)
+
+
 # --------------------------------------------------------------------- decode
 @pytest.mark.parametrize("N,Hq,Hkv,D,dtype", [(3, 8, 2, 128, BF16), (1, 4, 1, 128, BF16), (20, 8, 2, 128, BF16),
                                               (5, 6, 3, 64, BF16), (3, 4, 2, 64, F32), (2, 2, 1, 40, BF16)])
