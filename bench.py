@@ -237,6 +237,29 @@ def time_region(fn, steps: int, warmup: int) -> float:
     return (time.perf_counter() - t0) / steps
 
 
+def capture_step(pb: "PrefillBench"):
+    """One step (every launch of it) captured into a HIP graph, so that the timed region
+    measures the GPU and not the Python loop around 40 launches of 20-50 us each.  The replay
+    is checked against the eager step before it is used."""
+    pb.step()
+    torch.cuda.synchronize()
+    ref = pb.out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            pb.step()
+    torch.cuda.synchronize()
+    for rep in range(2):
+        pb.out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        if not torch.equal(pb.out, ref):
+            raise RuntimeError("graph replay %d of the step differs from the eager step" % rep)
+    return graph
+
+
 def cpu_baseline(pb: PrefillBench, budget_s: float = 15.0) -> dict:
     """The oracle, as it stands, on a bounded sample of the headline workload."""
     import oracle
@@ -277,6 +300,7 @@ def main() -> int:
     ap.add_argument("--sync-interval", type=int, default=None, help="override H of the workload")
     ap.add_argument("--no-aggregate", action="store_true", help="skip fedattn_aggregate_kv in sync blocks")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode measurement")
+    ap.add_argument("--no-graph", action="store_true", help="time the step launched from Python, not a graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=8, help="decode steps timed (spread over the 256)")
     ap.add_argument("--data-blocks", type=int, default=None, help="distinct input blocks kept resident")
@@ -294,9 +318,17 @@ def main() -> int:
     if nd is None and args.workload != "cfg2_llama8b_prefill":
         nd = 4   # 336 MB (cfg3) / 0.8 GB (cfg5) of inputs per block: keep a few distinct ones
     pb = PrefillBench(args.workload, nd, args.sync_interval, aggregate=not args.no_aggregate)
-    sec = time_region(pb.step, args.steps, args.warmup)
+    for _ in range(2):
+        pb.step()   # first launches set kernel attributes; keep that out of the capture
+    sec_eager = time_region(pb.step, args.steps, args.warmup)
+    if args.no_graph:
+        sec = sec_eager
+    else:
+        graph = capture_step(pb)
+        sec = time_region(graph.replay, args.steps, args.warmup)
     tflops = pb.flops_step / sec / 1e12
-    log("%s: %.3f ms/step, %.1f useful TFLOP/s" % (pb.w.name, sec * 1e3, tflops))
+    log("%s: %.3f ms/step, %.1f useful TFLOP/s (%s; launched from Python: %.3f ms/step)"
+        % (pb.w.name, sec * 1e3, tflops, "eager" if args.no_graph else "HIP graph replay", sec_eager * 1e3))
 
     # dominant kernel: HIP events around every prefill launch, same steps again
     ms = pb.kernel_times(min(args.steps, 10))
@@ -335,8 +367,10 @@ def main() -> int:
               "config": {"workload": pb.w.name, "participants": pb.w.n_participants,
                          "seg_lens": [int(x) for x in pb.w.seg_lens], "blocks": pb.M, "sync_interval": pb.H,
                          "q_heads": pb.w.n_q_heads, "kv_heads": pb.w.n_kv_heads, "head_dim": pb.w.head_dim,
-                         "launch": "one fedattn_prefill per block, fedattn_aggregate_kv before each sync block"
-                                   if pb.aggregate else "one fedattn_prefill per block"},
+                         "launch": ("one fedattn_prefill per block, fedattn_aggregate_kv before each sync block"
+                                    if pb.aggregate else "one fedattn_prefill per block")
+                                   + ("" if args.no_graph else "; the step's launches replayed from a HIP graph"),
+                         "ms_per_step_launched_from_python": sec_eager * 1e3},
               "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS,
               "roofline": roof,
               "analytic_cost_per_participant": cost.as_dict()}

@@ -449,6 +449,61 @@ def test_decode_blocks_equals_per_block_calls():
 
 
 # ------------------------------------------------------------------ aggregate
+def test_hip_graph_replays_match_eager():
+    """A sequence of the library's launches (aggregate, local and sync prefill, sparse prefill with
+    its list kernels, a decoding step over several blocks) captured in a HIP graph: every replay,
+    with eager work and synchronisations in between, must reproduce the eager results bit for bit."""
+    N, Hq, Hkv, D, M, H = 3, 8, 2, 128, 4, 2
+    seg = np.array([0, 100, 260, 420], dtype=np.int32)
+    total = 420
+    g = np.random.default_rng(81)
+    mk = lambda *s: fi.round_to_bf16(g.standard_normal(s).astype(np.float32))
+    q, k, v = dev(mk(M, total, Hq, D), BF16), dev(mk(M, total, Hkv, D), BF16), dev(mk(M, total, Hkv, D), BF16)
+    p = fa.make_params(N, Hq, Hkv, D, H, BF16)
+    out = torch.zeros_like(q)
+    out_sparse = torch.zeros_like(q[0])
+    kg, vg = torch.empty_like(k[0]), torch.empty_like(v[0])
+    flags = torch.from_numpy((g.random(total) < 0.4).astype(np.uint8)).cuda()
+    ws_p = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_PREFILL, total, 1), dtype=torch.uint8, device="cuda")
+    lens = np.array([100, 130, 160], dtype=np.int32)
+    qd = dev(mk(M, N, Hq, D), BF16)
+    od = torch.zeros_like(qd)
+    ws_d = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, total), dtype=torch.uint8, device="cuda")
+
+    def sequence():
+        for b in range(M):
+            kk, vv = k[b], v[b]
+            if fa.fedattn_is_sync_block(H, b):
+                fa.fedattn_aggregate_kv(p, [k[b][seg[i]:seg[i + 1]] for i in range(N)],
+                                        [v[b][seg[i]:seg[i + 1]] for i in range(N)], seg, kg, vg)
+                kk, vv = kg, vg
+            fa.fedattn_prefill(p, b, q[b], kk, vv, out[b], seg)
+        fa.fedattn_prefill(p, 1, q[1], k[1], v[1], out_sparse, seg, keep_chunks=flags, chunk_tokens=1, workspace=ws_p)
+        fa.fedattn_decode_blocks(p, 0, M, qd, k, v, od, qd[0].numel(), k[0].numel(), seg, lens, workspace=ws_d)
+
+    say("graph: eager reference")
+    sequence()
+    torch.cuda.synchronize()
+    ref = [out.clone(), out_sparse.clone(), od.clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sequence()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for t in (out, out_sparse, od):
+            t.fill_(float("nan"))
+        ws_d.fill_(0xAB)                      # eager work between the replays, on the workspace too
+        torch.cuda.synchronize()
+        say("graph: replay %d" % rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want, name in zip((out, out_sparse, od), ref, ("prefill", "sparse prefill", "decode")):
+            assert torch.equal(got, want), "graph replay %d: %s differs from the eager run" % (rep, name)
+
+
 @pytest.mark.parametrize("dtype", [BF16, F32])
 def test_aggregate_kv_bit_exact(dtype):
     seg = np.array([0, 77, 77, 300, 1325], dtype=np.int32)
