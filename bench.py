@@ -226,6 +226,44 @@ class DecodeBench:
         return e0.elapsed_time(e1)
 
 
+def end_to_end_leg(steps: int) -> dict:
+    """The end-to-end configuration: the 8-block mini-Transformer (d_model 2048, feed-forward 5632,
+    16/4 heads of 128) through the FedAttn schedule on 16 x 4096 tokens, sparse exchange in the
+    sync blocks.  One forward = 8 blocks; GEMMs go to the GEMM library, everything else runs in
+    this library's kernels.  Reported beside the headline, not part of it."""
+    from paper_2511_02647_amd.block import BlockBuffers, BlockWeights, block_forward
+    w = fi.workload("cfg5_sparse_sync")
+    d_model, hidden = 2048, 5632
+    seg, T = w.seg_offsets, w.total_tokens
+    p = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, w.sync_interval, torch.bfloat16)
+    buf = BlockBuffers(p, T, d_model, hidden, chunk_tokens=w.chunk_tokens)
+    weights = []
+    for b in range(w.n_blocks):
+        wt = fi.block_weights(w, b, d_model, hidden)
+        weights.append(BlockWeights(*(to_dev_bf16(wt[k]) for k in ("qkv", "o", "gate_up", "down"))))
+    sync = [fa.fedattn_is_sync_block(w.sync_interval, b) for b in range(w.n_blocks)]
+    keep = [torch.from_numpy(fi.keep_chunks(w, t)).to("cuda") for t in range(w.n_blocks // w.sync_interval)]
+    x0 = torch.from_numpy(fi.hidden_input(w, d_model).astype(np.float32)).to("cuda")
+    x = torch.empty_like(x0)
+
+    def forward():
+        x.copy_(x0)
+        for b in range(w.n_blocks):
+            kc = keep[b // w.sync_interval] if sync[b] else None
+            block_forward(p, b, x, weights[b], seg, buf, keep_chunks=kc, chunk_tokens=w.chunk_tokens if kc is not None else 0)
+
+    sec = time_region(forward, steps, 1)
+    fl_attn = 0.0
+    for b in range(w.n_blocks):
+        kt = keep_tokens(fi.keep_chunks(w, b // w.sync_interval), seg, w.chunk_tokens) if sync[b] else None
+        fl_attn += 4.0 * w.head_dim * w.n_q_heads * visible_pairs(seg, sync[b], kt)
+    Hq, Hkv, D = w.n_q_heads, w.n_kv_heads, w.head_dim
+    fl_gemm = w.n_blocks * 2.0 * T * (d_model * (Hq + 2 * Hkv) * D + Hq * D * d_model + d_model * 2 * hidden + hidden * d_model)
+    return {"workload": "cfg5 end to end: 8 blocks, d_model 2048, 16 x 4096 tokens, H = 2, 25 % of 64-token chunks exchanged",
+            "ms_per_forward": sec * 1e3, "attention_tflop": fl_attn / 1e12, "gemm_tflop": fl_gemm / 1e12,
+            "tflops_all": (fl_attn + fl_gemm) / sec / 1e12, "finite": bool(torch.isfinite(x).all().item())}
+
+
 def time_region(fn, steps: int, warmup: int) -> float:
     for _ in range(warmup):
         fn()
@@ -301,6 +339,8 @@ def main() -> int:
     ap.add_argument("--no-aggregate", action="store_true", help="skip fedattn_aggregate_kv in sync blocks")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode measurement")
     ap.add_argument("--no-graph", action="store_true", help="time the step launched from Python, not a graph replay")
+    ap.add_argument("--end-to-end", action="store_true",
+                    help="also run the 8-block mini-Transformer of the end-to-end configuration (adds ~20 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=8, help="decode steps timed (spread over the 256)")
     ap.add_argument("--data-blocks", type=int, default=None, help="distinct input blocks kept resident")
@@ -413,6 +453,13 @@ def main() -> int:
         log("decode: %.0f GB/s by events (all-local %.0f, all-sync %.0f), %.0f GB/s end to end"
             % (dec["roofline"]["achieved"], dec["roofline"]["local_GBps"], dec["roofline"]["sync_GBps"],
                dec["end_to_end_GBps"]))
+
+    if args.end_to_end:
+        torch.cuda.empty_cache()
+        result["end_to_end"] = end_to_end_leg(3)
+        log("end to end: %.1f ms per 8-block forward (%.2f TFLOP attention + %.2f TFLOP GEMM -> %.0f TFLOP/s)"
+            % (result["end_to_end"]["ms_per_forward"], result["end_to_end"]["attention_tflop"],
+               result["end_to_end"]["gemm_tflop"], result["end_to_end"]["tflops_all"]))
 
     print(json.dumps(result))
     return 0

@@ -132,6 +132,25 @@ def prefill_block(w: Workload, block: int, seed: int = DEFAULT_SEED,
     return q, k, v
 
 
+def hidden_input(w: Workload, d_model: int, seed: int = DEFAULT_SEED, total: Optional[int] = None) -> np.ndarray:
+    """x0 [total, d_model] ~ N(0, 1), bf16-valued: the input of the first block of the
+    end-to-end configuration."""
+    t = w.total_tokens if total is None else total
+    return normal_tensor(w, seed, 0, _T_X, (t, d_model), sigma=1.0)
+
+
+def block_weights(w: Workload, block: int, d_model: int, hidden: int, seed: int = DEFAULT_SEED,
+                  sigma: float = 0.02) -> dict:
+    """Weights of one decoder block of the end-to-end configuration, y = x @ W layouts, N(0, sigma^2)
+    rounded to bf16: qkv [d_model, (Hq + 2 Hkv) D], o [Hq D, d_model], gate_up [d_model, 2 hidden]
+    (gate columns first), down [hidden, d_model]."""
+    g = stream(seed, w.wid, block, _T_W)
+    Hq, Hkv, D = w.n_q_heads, w.n_kv_heads, w.head_dim
+    mk = lambda *shape: round_to_bf16((g.standard_normal(size=shape, dtype=np.float32) * np.float32(sigma)))
+    return {"qkv": mk(d_model, (Hq + 2 * Hkv) * D), "o": mk(Hq * D, d_model),
+            "gate_up": mk(d_model, 2 * hidden), "down": mk(hidden, d_model)}
+
+
 def decode_cache_block(w: Workload, block: int, seed: int = DEFAULT_SEED) -> Tuple[np.ndarray, np.ndarray]:
     """K and V caches [capacity_total,Hkv,D] of one block, filled for every row
     up to capacity (step s reads the first prompt+s+1 rows of each segment)."""

@@ -178,6 +178,34 @@ fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* co
                                     const void* const* v_local, const int32_t* seg_offsets,
                                     void* k_global, void* v_global, void* stream);
 
+/*
+ * Element-wise pieces of the decoder block around the attention operator, for the end-to-end
+ * configuration (a block is attention and a feed-forward network, each with a residual
+ * connection and a normalisation: Section III-B; the local forward of Section IV-A):
+ *   x += W_O Attention(RoPE(RMSNorm(x) W_QKV));  x += W_down (silu(gate) * up),
+ *   [gate up] = RMSNorm(x) W_gate_up.
+ * The matrix products are plain GEMMs and stay with the caller; these four passes are the
+ * rest.  Residual stream x in fp32, every other tensor bf16, all device pointers, 16-byte
+ * aligned, contiguous rows.
+ *
+ * fedattn_rmsnorm: out[r] = bf16(x[r] / sqrt(mean_j x[r][j]^2 + eps)), unit gain;
+ *   x fp32 [rows, d_model], out bf16 [rows, d_model]; d_model a multiple of 4.
+ * fedattn_rope_split_qkv: splits the fused projection qkv bf16 [tokens, (Hq + 2 Hkv) D]
+ *   (q heads, then k heads, then v heads) into q [tokens,Hq,D], k,v [tokens,Hkv,D] and
+ *   applies the rotary embedding to q and k: element i < D/2 is paired with i + D/2 and the
+ *   pair is rotated by pos * theta^(-2i/D).  pos: device int32[tokens], or NULL for
+ *   pos[t] = t (the index in the global sequence).  D a multiple of 8.
+ * fedattn_swiglu: out[r][f] = bf16(silu(gate_up[r][f]) * gate_up[r][hidden + f]);
+ *   gate_up bf16 [rows, 2 hidden], out bf16 [rows, hidden]; hidden a multiple of 8.
+ * fedattn_residual_add: x[i] += y[i]; x fp32, y bf16, n elements (a multiple of 4).
+ */
+fedattn_status fedattn_rmsnorm(const float* x, void* out, int64_t rows, int32_t d_model, float eps, void* stream);
+fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float theta,
+                                      void* stream);
+fedattn_status fedattn_swiglu(const void* gate_up, void* out, int64_t rows, int32_t hidden, void* stream);
+fedattn_status fedattn_residual_add(float* x, const void* y, int64_t n, void* stream);
+
 /* Reason of the calling thread's most recent failure ("" if none). */
 const char* fedattn_last_error(void);
 

@@ -25,6 +25,7 @@ FEDATTN_MAX_PARTICIPANTS = 128
 
 EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill",
            "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_aggregate_kv",
+           "fedattn_rmsnorm", "fedattn_rope_split_qkv", "fedattn_swiglu", "fedattn_residual_add",
            "fedattn_last_error", "fedattn_version")
 
 
@@ -69,6 +70,15 @@ def load():
     lib.fedattn_decode_blocks.restype = ctypes.c_int
     lib.fedattn_aggregate_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.fedattn_aggregate_kv.restype = ctypes.c_int
+    fl = ctypes.c_float
+    lib.fedattn_rmsnorm.argtypes = [vp, vp, i64, i32, fl, vp]
+    lib.fedattn_rmsnorm.restype = ctypes.c_int
+    lib.fedattn_rope_split_qkv.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, fl, vp]
+    lib.fedattn_rope_split_qkv.restype = ctypes.c_int
+    lib.fedattn_swiglu.argtypes = [vp, vp, i64, i32, vp]
+    lib.fedattn_swiglu.restype = ctypes.c_int
+    lib.fedattn_residual_add.argtypes = [vp, vp, i64, vp]
+    lib.fedattn_residual_add.restype = ctypes.c_int
     lib.fedattn_last_error.restype = ctypes.c_char_p
     lib.fedattn_version.restype = ctypes.c_char_p
     _lib = lib
@@ -215,3 +225,41 @@ def fedattn_aggregate_kv(params: fedattn_params, k_local: Sequence[Optional[torc
                 arr[i] = t.data_ptr()
     _check(load().fedattn_aggregate_kv(ctypes.byref(params), kp, vp, seg.ctypes.data_as(ctypes.c_void_p),
                                        _dev(k_global, "k_global"), _dev(v_global, "v_global"), _stream(stream)))
+
+
+def fedattn_rmsnorm(x: torch.Tensor, out: torch.Tensor, eps: float = 1e-6, stream=None) -> None:
+    """x fp32 [rows, d_model] -> out bf16 [rows, d_model]."""
+    if x.dtype != torch.float32 or out.dtype != torch.bfloat16 or x.shape != out.shape or x.dim() != 2:
+        raise TypeError("rmsnorm: x fp32 [rows, d_model], out bf16 of the same shape")
+    _check(load().fedattn_rmsnorm(_dev(x, "x"), _dev(out, "out"), x.shape[0], x.shape[1], float(eps), _stream(stream)))
+
+
+def fedattn_rope_split_qkv(qkv: torch.Tensor, pos: Optional[torch.Tensor], q: torch.Tensor, k: torch.Tensor,
+                           v: torch.Tensor, theta: float = 10000.0, stream=None) -> None:
+    """qkv bf16 [T, (Hq + 2 Hkv) D] -> q [T,Hq,D], k,v [T,Hkv,D] (bf16), q and k rotated; pos int32 [T] or None."""
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    if qkv.shape != (T, (Hq + 2 * Hkv) * D) or k.shape != (T, Hkv, D) or v.shape != (T, Hkv, D):
+        raise ValueError("rope: shapes of qkv, q, k, v do not fit together")
+    if any(t.dtype != torch.bfloat16 for t in (qkv, q, k, v)):
+        raise TypeError("rope: qkv, q, k, v must be bf16")
+    if pos is not None and (pos.dtype != torch.int32 or pos.shape != (T,)):
+        raise TypeError("rope: pos must be int32 [tokens]")
+    _check(load().fedattn_rope_split_qkv(_dev(qkv, "qkv"), _dev(pos, "pos"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                                         T, Hq, Hkv, D, float(theta), _stream(stream)))
+
+
+def fedattn_swiglu(gate_up: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """gate_up bf16 [rows, 2 F] -> out bf16 [rows, F]."""
+    if gate_up.dim() != 2 or out.shape != (gate_up.shape[0], gate_up.shape[1] // 2) or gate_up.shape[1] % 2:
+        raise ValueError("swiglu: gate_up [rows, 2 F], out [rows, F]")
+    if gate_up.dtype != torch.bfloat16 or out.dtype != torch.bfloat16:
+        raise TypeError("swiglu: bf16 tensors")
+    _check(load().fedattn_swiglu(_dev(gate_up, "gate_up"), _dev(out, "out"), out.shape[0], out.shape[1], _stream(stream)))
+
+
+def fedattn_residual_add(x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    """x fp32 += y bf16, same shape."""
+    if x.dtype != torch.float32 or y.dtype != torch.bfloat16 or x.shape != y.shape:
+        raise TypeError("residual_add: x fp32, y bf16, same shape")
+    _check(load().fedattn_residual_add(_dev(x, "x"), _dev(y, "y"), x.numel(), _stream(stream)))

@@ -420,6 +420,58 @@ fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* co
   return FEDATTN_OK;
 }
 
+// ---- element-wise pieces of the decoder block around the attention ----------------------
+namespace {
+constexpr int64_t kMaxGrid = 0x7fffffffLL;
+}
+
+fedattn_status fedattn_rmsnorm(const float* x, void* out, int64_t rows, int32_t d_model, float eps, void* stream) {
+  if (rows < 0 || d_model <= 0 || d_model % 4 != 0) return fail(FEDATTN_EINVAL, "rmsnorm: rows >= 0, d_model a positive multiple of 4");
+  if (!(eps >= 0.f)) return fail(FEDATTN_EINVAL, "rmsnorm: eps must be non-negative");
+  if (rows == 0) return FEDATTN_OK;
+  if (!x || !out || !aligned16(x) || !aligned16(out)) return fail(FEDATTN_EINVAL, "rmsnorm: x and out must be non-NULL and 16-byte aligned");
+  if ((rows + 3) / 4 > kMaxGrid) return fail(FEDATTN_EUNSUPPORTED, "rmsnorm: too many rows");
+  hipError_t e = launch_rmsnorm(x, out, rows, d_model, eps, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "rmsnorm: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
+fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float theta,
+                                      void* stream) {
+  if (tokens < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0 || head_dim % 8 != 0)
+    return fail(FEDATTN_EINVAL, "rope: tokens >= 0, positive head counts, head_dim a positive multiple of 8");
+  if (!(theta > 1.f)) return fail(FEDATTN_EINVAL, "rope: theta must exceed 1");
+  if (tokens == 0) return FEDATTN_OK;
+  if (!qkv || !q || !k || !v || !aligned16(qkv) || !aligned16(q) || !aligned16(k) || !aligned16(v))
+    return fail(FEDATTN_EINVAL, "rope: qkv, q, k and v must be non-NULL and 16-byte aligned");
+  if (tokens * (head_dim / 8) / 256 + 1 > kMaxGrid) return fail(FEDATTN_EUNSUPPORTED, "rope: too many tokens");
+  hipError_t e = launch_rope_split(qkv, pos, q, k, v, tokens, n_q_heads, n_kv_heads, head_dim, theta,
+                                   reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "rope: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
+fedattn_status fedattn_swiglu(const void* gate_up, void* out, int64_t rows, int32_t hidden, void* stream) {
+  if (rows < 0 || hidden <= 0 || hidden % 8 != 0) return fail(FEDATTN_EINVAL, "swiglu: rows >= 0, hidden a positive multiple of 8");
+  if (rows == 0) return FEDATTN_OK;
+  if (!gate_up || !out || !aligned16(gate_up) || !aligned16(out)) return fail(FEDATTN_EINVAL, "swiglu: gate_up and out must be non-NULL and 16-byte aligned");
+  if (rows * (hidden / 8) / 256 + 1 > kMaxGrid) return fail(FEDATTN_EUNSUPPORTED, "swiglu: too many elements");
+  hipError_t e = launch_swiglu(gate_up, out, rows, hidden, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "swiglu: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
+fedattn_status fedattn_residual_add(float* x, const void* y, int64_t n, void* stream) {
+  if (n < 0 || n % 4 != 0) return fail(FEDATTN_EINVAL, "residual_add: n must be a non-negative multiple of 4");
+  if (n == 0) return FEDATTN_OK;
+  if (!x || !y || !aligned16(x) || !aligned16(y)) return fail(FEDATTN_EINVAL, "residual_add: x and y must be non-NULL and 16-byte aligned");
+  if (n / 4 / 256 + 1 > kMaxGrid) return fail(FEDATTN_EUNSUPPORTED, "residual_add: too many elements");
+  hipError_t e = launch_residual_add(x, y, n, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "residual_add: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
 const char* fedattn_last_error(void) { return g_err; }
 
 const char* fedattn_version(void) { return "fedattn-gfx950 0.1"; }

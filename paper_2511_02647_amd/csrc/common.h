@@ -92,6 +92,11 @@ hipError_t launch_pack_kept_rows(const PrefillArgs& a, int32_t* kept_rows, int32
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_zero_counters(int32_t* counters, int n, hipStream_t s);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t s);
+hipError_t launch_rmsnorm(const float* x, void* out, int64_t rows, int d_model, float eps, hipStream_t s);
+hipError_t launch_rope_split(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens, int Hq,
+                             int Hkv, int D, float theta, hipStream_t s);
+hipError_t launch_swiglu(const void* gate_up, void* out, int64_t rows, int F, hipStream_t s);
+hipError_t launch_residual_add(float* x, const void* y, int64_t n, hipStream_t s);
 
 // Algorithm 1: block m = Ht + h (1-based) is the global-attention block iff h = H.
 __host__ __device__ inline bool sync_block_rule(int32_t H, int32_t block_idx) {

@@ -1,0 +1,157 @@
+"""The decoder block around the attention (end-to-end configuration) on the GPU against the
+fp64 block oracle: the four element-wise kernels one by one, then whole blocks."""
+import numpy as np
+import pytest
+import torch
+
+import fedattn_inputs as fi
+import paper_2511_02647_amd as fa
+from paper_2511_02647_amd.block import BlockBuffers, BlockWeights, block_forward
+import oracle
+from oracle import block as ob
+from gpu_util import check, dev, host, say
+
+pytestmark = pytest.mark.gpu
+BF16 = torch.bfloat16
+
+ULP = 2.0 ** -8      # spacing of bf16 relative to the value (one unit in the last place, upper bound)
+
+
+def _bf16_close(got, ref_unrounded, what, slack=1.0):
+    """A bf16 result computed in fp32 from exactly known inputs: within one bf16 step of the
+    unrounded fp64 value (half a step of rounding + a flip when fp32 arithmetic lands on the
+    other side of a rounding boundary)."""
+    err = np.abs(got - ref_unrounded)
+    tol = slack * ULP * np.abs(ref_unrounded) + 1e-6
+    worst = float((err / tol).max())
+    print("[parity] %-60s max err / (one bf16 step) = %.3f" % (what, worst), flush=True)
+    assert worst <= 1.0, what
+
+
+def test_rmsnorm_kernel():
+    g = np.random.default_rng(1)
+    for rows, d in ((37, 2048), (5, 96), (1, 4)):
+        x = (g.standard_normal((rows, d)) * 3).astype(np.float32)
+        tx = torch.from_numpy(x).cuda()
+        out = torch.full((rows, d), float("nan"), dtype=BF16, device="cuda")
+        say("rmsnorm %dx%d" % (rows, d))
+        fa.fedattn_rmsnorm(tx, out)
+        torch.cuda.synchronize()
+        _bf16_close(host(out), ob.rmsnorm(x), "rmsnorm %dx%d" % (rows, d))
+
+
+def test_rope_split_kernel():
+    g = np.random.default_rng(2)
+    for T, Hq, Hkv, D in ((50, 8, 4, 128), (7, 3, 1, 64), (3, 2, 2, 8)):
+        qkv = fi.round_to_bf16(g.standard_normal((T, (Hq + 2 * Hkv) * D)).astype(np.float32))
+        tq = dev(qkv, BF16)
+        q = torch.full((T, Hq, D), float("nan"), dtype=BF16, device="cuda")
+        k = torch.full((T, Hkv, D), float("nan"), dtype=BF16, device="cuda")
+        v = torch.full((T, Hkv, D), float("nan"), dtype=BF16, device="cuda")
+        for pos in (None, g.integers(0, 70000, size=T).astype(np.int32)):
+            say("rope T=%d Hq=%d Hkv=%d D=%d pos=%s" % (T, Hq, Hkv, D, "given" if pos is not None else "index"))
+            fa.fedattn_rope_split_qkv(tq, None if pos is None else torch.from_numpy(pos).cuda(), q, k, v)
+            torch.cuda.synchronize()
+            p = np.arange(T) if pos is None else pos
+            x64 = qkv.astype(np.float64)
+            rq = ob.rope(x64[:, :Hq * D].reshape(T, Hq, D), p)
+            rk = ob.rope(x64[:, Hq * D:(Hq + Hkv) * D].reshape(T, Hkv, D), p)
+            # the rotation mixes two inputs: allow the step of the larger one
+            for got, ref, src, nm in ((host(q), rq, x64[:, :Hq * D].reshape(T, Hq, D), "q"),
+                                      (host(k), rk, x64[:, Hq * D:(Hq + Hkv) * D].reshape(T, Hkv, D), "k")):
+                mag = np.sqrt(src[..., :D // 2] ** 2 + src[..., D // 2:] ** 2)
+                mag = np.concatenate([mag, mag], axis=-1)
+                err = np.abs(got - ref)
+                worst = float((err / (ULP * mag + 1e-6)).max())
+                print("[parity] rope %s D=%d: max err / (one bf16 step of the pair) = %.3f" % (nm, D, worst), flush=True)
+                assert worst <= 1.0
+            assert np.array_equal(host(v), x64[:, (Hq + Hkv) * D:].reshape(T, Hkv, D)), "v must be copied bit for bit"
+
+
+def test_swiglu_and_residual_kernels():
+    g = np.random.default_rng(3)
+    rows, F = 29, 5632
+    gu = fi.round_to_bf16((g.standard_normal((rows, 2 * F)) * 3).astype(np.float32))
+    out = torch.full((rows, F), float("nan"), dtype=BF16, device="cuda")
+    say("swiglu")
+    fa.fedattn_swiglu(dev(gu, BF16), out)
+    torch.cuda.synchronize()
+    ref = ob.swiglu(gu[:, :F].astype(np.float64), gu[:, F:].astype(np.float64))
+    _bf16_close(host(out), ref, "swiglu %dx%d" % (rows, F))
+    x = g.standard_normal((rows, 2048)).astype(np.float32)
+    y = fi.round_to_bf16(g.standard_normal((rows, 2048)).astype(np.float32))
+    tx = torch.from_numpy(x).cuda()
+    say("residual add")
+    fa.fedattn_residual_add(tx, dev(y, BF16))
+    torch.cuda.synchronize()
+    assert np.array_equal(tx.cpu().numpy(), x + y), "fp32 residual add must be exactly rounded"
+
+
+def test_block_op_errors_are_return_codes():
+    x = torch.zeros(4, 6, device="cuda")
+    with pytest.raises(fa.FedAttnError) as e:
+        fa.fedattn_rmsnorm(x, torch.zeros(4, 6, dtype=BF16, device="cuda"))     # d_model not a multiple of 4
+    assert e.value.status == fa.FEDATTN_EINVAL
+
+
+def _run_blocks(w, seg, d_model, hidden, n_blocks, total, keep_for_block):
+    """GPU blocks 0..n_blocks-1 on x0, with the oracle teacher-forced block by block."""
+    N = len(seg) - 1
+    p = fa.make_params(N, w.n_q_heads, w.n_kv_heads, w.head_dim, w.sync_interval, BF16)
+    buf = BlockBuffers(p, total, d_model, hidden, chunk_tokens=w.chunk_tokens)
+    x0 = fi.hidden_input(w, d_model, total=total)
+    x = torch.from_numpy(x0.astype(np.float32)).cuda()
+    x_oracle_e2e = x0.astype(np.float64)
+    kw = dict(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim)
+    for b in range(n_blocks):
+        wts = fi.block_weights(w, b, d_model, hidden)
+        bw = BlockWeights(*(dev(wts[k], BF16) for k in ("qkv", "o", "gate_up", "down")))
+        sync = oracle.is_sync_block(w.sync_interval, b)
+        flags = keep_for_block(b) if sync else None
+        kt = None if flags is None else oracle.expand_keep_chunks(flags, seg, w.chunk_tokens)
+        x_in = x.cpu().numpy().astype(np.float64)
+        say("block %d (%s%s), %d tokens, d_model %d" % (b, "sync" if sync else "local", ", sparse" if kt is not None else "", total, d_model))
+        res = block_forward(p, b, x, bw, seg, buf, keep_chunks=None if flags is None else torch.from_numpy(flags).cuda(),
+                            chunk_tokens=w.chunk_tokens if flags is not None else 0)
+        torch.cuda.synchronize()
+        # gate (i), teacher-forced: the attention of the GPU's own q, k, v, to the attention tolerance
+        ref_attn = oracle.attend_block(host(res["q"]), host(res["k"]), host(res["v"]), seg, is_sync=sync, keep_tok=kt)
+        check(host(res["attn"]), ref_attn, BF16, "block %d attention on the device's q, k, v" % b)
+        # the whole block from the GPU's block input, oracle rounding at the bf16 interfaces
+        ref = ob.block_forward(x_in, wts, seg, is_sync=sync, keep_tok=kt, round_fn=fi.round_to_bf16, **kw)
+        got = x.cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref["out"])
+        print("[parity] block %d output vs oracle from the same input: max-abs %.3e mean-abs %.3e (|x| max %.2f)"
+              % (b, err.max(), err.mean(), np.abs(ref["out"]).max()), flush=True)
+        # Two bf16 updates (projection, feed-forward) of magnitude up to ~4 land on the fp32 stream;
+        # the device rounds fp32-accumulated sums, the oracle fp64 ones, and rounding flips upstream
+        # (normalised input, q/k/v, activations) shift the sums by a fraction of a bf16 step, so an
+        # update may come out one step (2^-8 |update|) apart: max <= 2 * 2^-8 * 4 + margin, mean about
+        # half a step of a unit-size update per update.
+        assert err.max() <= 5e-2 and err.mean() <= 3e-3, "block %d output" % b
+        x_oracle_e2e = ob.block_forward(x_oracle_e2e, wts, seg, is_sync=sync, keep_tok=kt, round_fn=fi.round_to_bf16, **kw)["out"]
+    # gate (ii), end to end: oracle carried through all blocks on its own
+    got = x.cpu().numpy().astype(np.float64)
+    err = np.abs(got - x_oracle_e2e)
+    print("[parity] %d blocks end to end: max-abs %.3e mean-abs %.3e" % (n_blocks, err.max(), err.mean()), flush=True)
+    assert err.max() <= 5e-2 * n_blocks and err.mean() <= 3e-3 * n_blocks   # the per-block bound, carried along
+
+
+def test_blocks_small_model():
+    w = fi.workload("cfg5_sparse_sync")          # 16/4 heads of 128, H = 2, 64-token keep chunks
+    seg = np.array([0, 100, 228, 420], dtype=np.int32)
+    g = np.random.default_rng(8)
+    nch = int(fi.chunk_counts(np.diff(seg), w.chunk_tokens).sum())
+    _run_blocks(w, seg, d_model=512, hidden=704, n_blocks=4, total=420,
+                keep_for_block=lambda b: (g.random(nch) < 0.5).astype(np.uint8))
+
+
+def test_blocks_end_to_end_configuration_scaled_down():
+    """The end-to-end configuration (d_model 2048, feed-forward 5632, 16/4 heads, H = 2, a quarter
+    of the 64-token chunks exchanged) at 16 x 256 tokens, two blocks (one local, one sparse sync)."""
+    w = fi.workload("cfg5_sparse_sync")
+    seg = (np.arange(17) * 256).astype(np.int32)
+    import dataclasses
+    small = dataclasses.replace(w, seg_lens=(256,) * 16)
+    _run_blocks(w, seg, d_model=2048, hidden=5632, n_blocks=2, total=4096,
+                keep_for_block=lambda b: fi.keep_chunks(small, b // w.sync_interval))
