@@ -193,9 +193,12 @@ def test_prefill_blocks_batched_equals_per_block():
         one = torch.full_like(tq[b], float("nan"))
         fa.fedattn_prefill(p, b, tq[b], tk[b], tv[b], one, seg)
         torch.cuda.synchronize()
-        assert torch.equal(one, out[b]), "batched launch differs from the per-block launch at block %d" % b
         ref = oracle.attend_block(*blocks[b], seg, is_sync=oracle.is_sync_block(H, b))
         check(host(out[b]), ref, BF16, "batched block %d" % b)
+        check(host(one), ref, BF16, "per-block launch of block %d" % b)
+        # the two launches may split the KV tiles differently (summation order), nothing more
+        assert (one.float() - out[b].float()).abs().max().item() <= 2.0 ** -7 * ref.__abs__().max(), \
+            "batched launch differs from the per-block launch at block %d" % b
 
 
 # ------------------------------------- variable sync schedules, exclusion, token-granular exchange
