@@ -315,6 +315,48 @@ def test_cfg5_sparse_sync_full_size():
                        what="cfg5 block %d" % b, salt=20 + b)
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes(case):
+    """Seeded random layouts: participants, ragged and empty segments, head grouping, head
+    dimension, causal or not, local / sync / sparse sync, and a decoding step on the same layout."""
+    g = np.random.default_rng(7000 + case)
+    N = int(g.integers(1, 12))
+    lens = g.integers(0, 300, size=N)
+    if g.random() < 0.5:
+        lens[g.integers(0, N)] = 0
+    if lens.sum() == 0:
+        lens[0] = 17
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(seg[-1])
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.choice([1, 2, 3]))
+    Hq = Hkv * int(g.choice([1, 2, 4, 8]))
+    causal = bool(g.random() < 0.7)
+    scale = float(g.choice([0.0, 0.05, 0.3]))
+    q, k, v = rand_block(8000 + case, total, Hq, Hkv, D, sigma=float(g.choice([0.5, 1.0])))
+    for sync in (0, 1):
+        say("random case %d: N=%d total=%d Hq=%d Hkv=%d D=%d causal=%d sync=%d" % (case, N, total, Hq, Hkv, D, causal, sync))
+        got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, causal=causal, sync_override=sync, scale=scale)
+        ref = oracle.attend_block(q, k, v, seg, is_sync=bool(sync), causal=causal, scale=scale if scale else None)
+        check(got, ref, BF16, "random case %d sync=%d" % (case, sync))
+    chunk = int(g.choice([1, 7, 64, 128]))
+    nch = int(fi.chunk_counts(np.diff(seg), chunk).sum())
+    flags = (g.random(nch) < g.choice([0.1, 0.5, 0.9])).astype(np.uint8)
+    say("random case %d: sparse sync, chunk %d" % (case, chunk))
+    got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, causal=causal, keep_chunks=flags, chunk_tokens=chunk)
+    ref = oracle.attend_block(q, k, v, seg, is_sync=True, causal=causal, keep_tok=oracle.expand_keep_chunks(flags, seg, chunk))
+    check(got, ref, BF16, "random case %d sparse chunk=%d" % (case, chunk))
+    # decoding step over the same buffers as caches
+    cache_lens = np.array([int(g.integers(0, l + 1)) for l in lens], dtype=np.int32)
+    prompt = np.minimum(cache_lens, g.integers(0, 300, size=N)).astype(np.int32)
+    qd, _, _ = rand_block(9000 + case, N, Hq, Hkv, D)
+    for sync, rl in [(0, None), (1, None), (1, prompt)]:
+        say("random case %d: decode sync=%d remote=%s" % (case, sync, rl is not None))
+        got = decode(qd, k, v, seg, cache_lens, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, remote_lens=rl, sync_override=sync)
+        ref = oracle.decode_step(qd, k, v, seg, cache_lens, is_sync=bool(sync), remote_lens=rl)
+        check(got, ref, BF16, "random case %d decode sync=%d remote=%s" % (case, sync, rl is not None))
+
+
 def test_offsets_beyond_32_bits():
     """One million tokens, 128 participants: byte offsets into q, k, v, out and the caches pass
     2^32 (q/out 8.6 GB, k/v 4.3 GB each).  Inputs of this size are drawn on the device; the
