@@ -12,6 +12,7 @@ namespace fedattn {
 constexpr int kMaxP = FEDATTN_MAX_PARTICIPANTS;
 constexpr int kKvTile = 64;    // KV rows per MFMA prefill tile; also the keep-list tile
 constexpr int kWaveRows = 32;  // query rows per wave in the MFMA prefill kernel
+constexpr int kMaxOrderedTiles = 512;  // query tiles of a launch that assigns them through an explicit order
 
 // Segment layout of the global sequence, passed by value in the kernel arguments
 // (read with scalar loads; no device copy of host arrays is needed).
@@ -47,8 +48,12 @@ struct PrefillArgs {
   int32_t n_q_tiles;
   int32_t n_cus;            // compute units of the device (launch shape heuristics)
   float scale;              // softmax scale
+  int32_t n_ordered;        // > 0: one workgroup per query tile, workgroup p takes tile_order[p] (MFMA kernel)
   SegLayout seg;
+  uint16_t tile_order[kMaxOrderedTiles];
 };
+
+static_assert(sizeof(PrefillArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 struct DecodeArgs {
   const void* q;

@@ -20,6 +20,7 @@
 //                 segment up to the diagonal.
 // Tiles entirely above the diagonal or in other participants' segments of a local
 // block are never visited; only diagonal and ragged tiles apply an element mask.
+#include <algorithm>
 #include <climits>
 #include <type_traits>
 
@@ -110,7 +111,11 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
   // block); a workgroup takes a heavy query tile and then its light mirror image so
   // that all workgroups carry the same load.
   int tile_a = -1, tile_b = -1;  // heavy tile, then its light partner (or none)
-  if (!causal) {
+  if (a.n_ordered > 0) {
+    // small causal launch: one query tile per workgroup, in the order the host laid out
+    if (p >= a.n_ordered) return;
+    tile_a = a.tile_order[p];
+  } else if (!causal) {
     if (p >= T) return;
     tile_a = T - 1 - p;
   } else if (is_sync) {
@@ -505,13 +510,16 @@ hipError_t launch_prefill_mfma_t(const PrefillArgs& a, dim3 grid, hipStream_t s)
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s) {
-  if (a.n_q_tiles == 0 || n_blocks == 0) return hipSuccess;
+hipError_t launch_prefill_mfma(const PrefillArgs& a_in, int n_blocks, hipStream_t s) {
+  if (a_in.n_q_tiles == 0 || n_blocks == 0) return hipSuccess;
+  PrefillArgs a = a_in;
+  a.n_ordered = 0;
   const int G = a.Hq / a.Hkv;
+  const int per_tile = a.Hkv * (G / a.heads_per_wg);  // workgroups per query tile (or pair)
   // causal: query tiles are paired; a local block pairs inside each segment, which
   // needs at least as many workgroups as the sequence-wide pairing of a sync block
-  const int wg_tiles = a.causal ? a.seg.pair_cum[a.seg.n] : a.n_q_tiles;
-  dim3 grid((unsigned)(wg_tiles * a.Hkv * (G / a.heads_per_wg)), (unsigned)n_blocks, 1);
+  int wg_tiles = a.causal ? a.seg.pair_cum[a.seg.n] : a.n_q_tiles;
+  dim3 grid((unsigned)(wg_tiles * per_tile), (unsigned)n_blocks, 1);
   // Fewer than two 4-wave workgroups per CU: 8-wave workgroups that split the KV tiles of a
   // query tile between two groups keep two wavefronts on every SIMD, at the price of a merge
   // through LDS per query tile and a heavier start.  That pays from about 16 KV tiles per
@@ -531,6 +539,31 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a, int n_blocks, hipStream_t s
       kv_tiles += q_tiles * ((mean_keys + kKvTile - 1) / kKvTile + (a.causal ? 1 : 0));
     }
     wide = kv_tiles >= 16 * (int64_t)wg_tiles;
+    // Not enough tiles per workgroup for the split, and every query tile can have a workgroup of
+    // its own with all of them resident at once (two per CU): drop the pairing.  Two unrelated
+    // 4-wave workgroups on a CU overlap each other's matrix and vector phases, which one
+    // workgroup walking a pair cannot do with itself.  Order: heavy half first, heaviest first;
+    // then the light half, lightest first, so that the workgroups that come to share a CU
+    // (index p and p + half, dispatched in order) carry about the same load together.
+    if (!wide && a.causal && a.n_q_tiles <= kMaxOrderedTiles && (int64_t)a.n_q_tiles * per_tile <= 2 * (int64_t)a.n_cus) {
+      struct Item { int tile, work; };
+      Item items[kMaxOrderedTiles];
+      int cnt = 0;
+      for (int n = 0; n < N; ++n) {
+        const int lo = a.seg.seg_off[n], hi = a.seg.seg_off[n + 1];
+        for (int t = a.seg.tile_cum[n]; t < a.seg.tile_cum[n + 1]; ++t) {
+          const int last = min(lo + (t - a.seg.tile_cum[n] + 1) * a.q_tile_rows, hi);  // one past the tile's last row
+          items[cnt++] = Item{t, (last - (is_sync ? 0 : lo) + kKvTile - 1) / kKvTile};
+        }
+      }
+      std::stable_sort(items, items + cnt, [](const Item& x, const Item& y) { return x.work > y.work; });
+      const int half = (cnt + 1) / 2;
+      for (int i = 0; i < half; ++i) a.tile_order[i] = (uint16_t)items[i].tile;
+      for (int i = half; i < cnt; ++i) a.tile_order[i] = (uint16_t)items[cnt - 1 - (i - half)].tile;
+      a.n_ordered = cnt;
+      wg_tiles = cnt;
+      grid.x = (unsigned)(wg_tiles * per_tile);
+    }
   }
   if (a.D == 128) return wide ? launch_prefill_mfma_t<128, 2>(a, grid, s) : launch_prefill_mfma_t<128, 1>(a, grid, s);
   return wide ? launch_prefill_mfma_t<64, 2>(a, grid, s) : launch_prefill_mfma_t<64, 1>(a, grid, s);
