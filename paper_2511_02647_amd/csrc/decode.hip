@@ -443,6 +443,62 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
   const int d4 = tid % D4, cg = tid / D4;  // blockDim = D4 * CG
   const int64_t cstride = a.cols;          // partial rows between consecutive chunks
 
+  if (c1 - c0 <= 16 * CG) {
+    // Few chunks (the usual case): one round trip.  Every thread requests its partial O rows
+    // and one chunk's (m, l) before anything is known about the weights.
+    const int nb = c1 - c0;
+    const float* po = a.part_o + ((base + c0) * cstride + col) * D + 4 * d4;
+    f32x4 part[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int i = cg + CG * u;
+      part[u] = i < nb ? *reinterpret_cast<const f32x4*>(po + i * cstride * D) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    float m_i = -INFINITY, l_i = 0.f;
+    if (tid < nb) {
+      const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + ((base + c0 + tid) * cstride + col) * 2);
+      m_i = ml[0];
+      l_i = ml[1];
+    }
+    float mm = wave_max(m_i);
+    if ((tid & 63) == 0) m_s[tid >> 6] = mm;
+    __syncthreads();
+    mm = -INFINITY;
+    for (int w = 0; w < (int)((blockDim.x + 63) >> 6); ++w) mm = fmaxf(mm, m_s[w]);
+    const float mu = (mm == -INFINITY) ? 0.f : mm;
+    if (tid < nb) {
+      w_s[tid] = __builtin_amdgcn_exp2f(m_i - mu);
+      l_s[tid] = l_i;
+    }
+    __syncthreads();
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int i = cg + CG * u;
+      if (i < nb) acc += part[u] * w_s[i];
+    }
+    acc_s[cg][d4] = acc;
+    if (tid == 0) {
+      float den = 0.f;
+      for (int i = 0; i < nb; ++i) den = fmaf(l_s[i], w_s[i], den);
+      m_s[8] = den;
+    }
+    __syncthreads();
+    if (cg == 0) {
+      const float dn = m_s[8];
+      const f32x4 sum = (acc_s[0][d4] + acc_s[1][d4]) + (acc_s[2][d4] + acc_s[3][d4]);
+      const f32x4 val = sum * (dn > 0.f ? 1.f / dn : 0.f);
+      T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * D + 4 * d4;
+      if constexpr (sizeof(T) == 2) {
+        const bf16x4 w4 = {(bf16_t)val[0], (bf16_t)val[1], (bf16_t)val[2], (bf16_t)val[3]};
+        *reinterpret_cast<u32x2*>(out) = __builtin_bit_cast(u32x2, w4);
+      } else {
+        *reinterpret_cast<f32x4*>(out) = val;
+      }
+    }
+    return;
+  }
+
   // row maximum over all chunks
   float mm = -INFINITY;
   for (int cc = c0 + tid; cc < c1; cc += blockDim.x) mm = fmaxf(mm, a.part_ml[((base + cc) * cstride + col) * 2]);
