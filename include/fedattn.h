@@ -33,6 +33,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+/* The entry points below are the library's only exported symbols. */
+#define FEDATTN_API __attribute__((visibility("default")))
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -65,14 +68,14 @@ typedef struct fedattn_params {
 /* Algorithm 1: with blocks numbered m = H t + h (1-based), block m runs global
  * attention iff h = H.  For the 0-based block_idx used here that is
  * H >= 1 && (block_idx + 1) % H == 0.  Returns 1 (sync block) or 0 (local). */
-int fedattn_is_sync_block(int32_t sync_interval, int32_t block_idx);
+FEDATTN_API int fedattn_is_sync_block(int32_t sync_interval, int32_t block_idx);
 
 /* Bytes of device workspace the given op needs (16-byte aligned start).
  *   FEDATTN_OP_PREFILL: `tokens` = total tokens; needed only when a keep-list is
  *     passed (chunk_tokens > 0); 0 otherwise.
  *   FEDATTN_OP_DECODE:  `tokens` = total cache capacity; chunk_tokens ignored.
  * Returns 0 on invalid params. */
-size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t tokens,
+FEDATTN_API size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t tokens,
                                int32_t chunk_tokens);
 
 /*
@@ -105,7 +108,7 @@ size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t
  *   workspace      device, >= fedattn_workspace_bytes(PREFILL); may be NULL when
  *                  keep_chunks is NULL.
  */
-fedattn_status fedattn_prefill(const fedattn_params* params, int32_t block_idx, const void* q,
+FEDATTN_API fedattn_status fedattn_prefill(const fedattn_params* params, int32_t block_idx, const void* q,
                                const void* k, const void* v, void* out,
                                const int32_t* seg_offsets, const uint8_t* keep_chunks,
                                int32_t chunk_tokens, int32_t sync_override, void* workspace,
@@ -118,7 +121,7 @@ fedattn_status fedattn_prefill(const fedattn_params* params, int32_t block_idx, 
  * exchange only.  Semantics per block are exactly those of fedattn_prefill.  For
  * workloads whose per-block work is too small to fill the GPU.
  */
-fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t block_idx0,
+FEDATTN_API fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t block_idx0,
                                       int32_t n_blocks, const void* q, const void* k,
                                       const void* v, void* out, int64_t q_block_stride,
                                       int64_t kv_block_stride, const int32_t* seg_offsets,
@@ -143,7 +146,7 @@ fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t bloc
  *                  chunk counters while the call's kernels run.  What it contains on entry
  *                  does not matter; calls that share a workspace must be ordered (same stream).
  */
-fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q,
+FEDATTN_API fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q,
                               const void* k_cache, const void* v_cache, void* out,
                               const int32_t* seg_offsets, const int32_t* seg_lens,
                               const int32_t* remote_lens, int32_t sync_override, void* workspace,
@@ -158,7 +161,7 @@ fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, c
  * of a model depend on each other); results equal n_blocks calls of fedattn_decode.
  * The workspace is reused from block to block in stream order.
  */
-fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+FEDATTN_API fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
                                      const void* q, const void* k_cache, const void* v_cache, void* out,
                                      int64_t q_block_stride, int64_t cache_block_stride,
                                      const int32_t* seg_offsets, const int32_t* seg_lens,
@@ -174,7 +177,7 @@ fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block
  * A pure copy; on one GPU a caller that already keeps the participants' K,V
  * back to back in global order can skip it.
  */
-fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* const* k_local,
+FEDATTN_API fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* const* k_local,
                                     const void* const* v_local, const int32_t* seg_offsets,
                                     void* k_global, void* v_global, void* stream);
 
@@ -199,18 +202,18 @@ fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* co
  *   gate_up bf16 [rows, 2 hidden], out bf16 [rows, hidden]; hidden a multiple of 8.
  * fedattn_residual_add: x[i] += y[i]; x fp32, y bf16, n elements (a multiple of 4).
  */
-fedattn_status fedattn_rmsnorm(const float* x, void* out, int64_t rows, int32_t d_model, float eps, void* stream);
-fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens,
+FEDATTN_API fedattn_status fedattn_rmsnorm(const float* x, void* out, int64_t rows, int32_t d_model, float eps, void* stream);
+FEDATTN_API fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens,
                                       int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float theta,
                                       void* stream);
-fedattn_status fedattn_swiglu(const void* gate_up, void* out, int64_t rows, int32_t hidden, void* stream);
-fedattn_status fedattn_residual_add(float* x, const void* y, int64_t n, void* stream);
+FEDATTN_API fedattn_status fedattn_swiglu(const void* gate_up, void* out, int64_t rows, int32_t hidden, void* stream);
+FEDATTN_API fedattn_status fedattn_residual_add(float* x, const void* y, int64_t n, void* stream);
 
 /* Reason of the calling thread's most recent failure ("" if none). */
-const char* fedattn_last_error(void);
+FEDATTN_API const char* fedattn_last_error(void);
 
 /* Library version string. */
-const char* fedattn_version(void);
+FEDATTN_API const char* fedattn_version(void);
 
 #ifdef __cplusplus
 }
