@@ -357,6 +357,54 @@ def test_random_shapes(case):
         check(got, ref, BF16, "random case %d decode sync=%d remote=%s" % (case, sync, rl is not None))
 
 
+@pytest.mark.parametrize("case", range(16))
+def test_random_mid_size_layouts(case):
+    """Seeded random layouts of up to 8 participants x 2600 tokens, checked on sampled rows: these
+    sizes reach every launch shape of the MFMA kernel (paired and one-tile workgroups, 4-wave and
+    8-wave split-KV workgroups), whole-tile and finer keep chunks, and decoding with chunked caches."""
+    g = np.random.default_rng(31000 + case)
+    N = int(g.integers(1, 9))
+    hi = int(g.choice([200, 700, 1500, 2600]))
+    lens = g.integers(0, hi, size=N)
+    if g.random() < 0.3:
+        lens[g.integers(0, N)] = 0
+    if g.random() < 0.3:
+        lens[:] = (lens // 64) * 64
+    if lens.sum() == 0:
+        lens[0] = 65
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(seg[-1])
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.choice([1, 2, 4, 8]))
+    Hq = Hkv * int(g.choice([1, 2, 4]))
+    causal = bool(g.random() < 0.75)
+    q, k, v = rand_block(32000 + case, total, Hq, Hkv, D)
+    rows, heads = fi.sample_rows(seg, Hq, 96, fi.DEFAULT_SEED, salt=300 + case)
+    for sync in (0, 1):
+        say("mid-size case %d: lens=%s Hq=%d Hkv=%d D=%d causal=%d sync=%d" % (case, lens.tolist(), Hq, Hkv, D, causal, sync))
+        got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, causal=causal, sync_override=sync)
+        ref = oracle.attend_rows(q, k, v, seg, rows, heads, is_sync=bool(sync), causal=causal)
+        check(got[rows, heads], ref, BF16, "mid-size case %d sync=%d" % (case, sync))
+    chunk = int(g.choice([1, 5, 16, 64, 128, 192]))
+    nch = int(fi.chunk_counts(np.diff(seg), chunk).sum())
+    flags = (g.random(nch) < g.choice([0.05, 0.25, 0.5, 0.95])).astype(np.uint8)
+    say("mid-size case %d: sparse sync, chunk %d" % (case, chunk))
+    got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=1, block=0, dtype=BF16, causal=causal, keep_chunks=flags, chunk_tokens=chunk)
+    ref = oracle.attend_rows(q, k, v, seg, rows, heads, is_sync=True, causal=causal,
+                             keep_tok=oracle.expand_keep_chunks(flags, seg, chunk))
+    check(got[rows, heads], ref, BF16, "mid-size case %d sparse chunk=%d" % (case, chunk))
+    cache_lens = np.array([int(g.integers(0, l + 1)) for l in lens], dtype=np.int32)
+    if g.random() < 0.5:
+        cache_lens = np.maximum(cache_lens, np.minimum(lens, 1)).astype(np.int32)   # no empty cache where there is room
+    prompt = np.minimum(cache_lens, g.integers(0, hi, size=N)).astype(np.int32)
+    qd, _, _ = rand_block(33000 + case, N, Hq, Hkv, D)
+    for sync, rl in [(0, None), (1, None), (1, prompt)]:
+        say("mid-size case %d: decode sync=%d remote=%s" % (case, sync, rl is not None))
+        got = decode(qd, k, v, seg, cache_lens, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, remote_lens=rl, sync_override=sync)
+        ref = oracle.decode_step(qd, k, v, seg, cache_lens, is_sync=bool(sync), remote_lens=rl)
+        check(got, ref, BF16, "mid-size case %d decode sync=%d remote=%s" % (case, sync, rl is not None))
+
+
 def test_offsets_beyond_32_bits():
     """One million tokens, 128 participants: byte offsets into q, k, v, out and the caches pass
     2^32 (q/out 8.6 GB, k/v 4.3 GB each).  Inputs of this size are drawn on the device; the
