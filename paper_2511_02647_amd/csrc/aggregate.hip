@@ -18,7 +18,20 @@ __global__ __launch_bounds__(256) void aggregate_kv_kernel(AggregateArgs a) {
   uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(is_v ? a.v_global : a.k_global) +
                                         (int64_t)lo * a.row_bytes);
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += stride) dst[u] = src[u];
+  // four loads in flight per thread before the first store: the copy is a chain of memory
+  // round trips otherwise (a launch moves a few MB, i.e. a handful of units per thread)
+  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += 4 * stride) {
+    // loads past the end re-read the last unit (no branch between the loads); their stores are skipped
+    const int64_t u1 = u + stride, u2 = u + 2 * stride, u3 = u + 3 * stride, last = units - 1;
+    const uint4 r0 = src[u];
+    const uint4 r1 = src[u1 < units ? u1 : last];
+    const uint4 r2 = src[u2 < units ? u2 : last];
+    const uint4 r3 = src[u3 < units ? u3 : last];
+    dst[u] = r0;
+    if (u1 < units) dst[u1] = r1;
+    if (u2 < units) dst[u2] = r2;
+    if (u3 < units) dst[u3] = r3;
+  }
 }
 
 }  // namespace
