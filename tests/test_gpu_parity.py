@@ -405,6 +405,32 @@ def test_random_mid_size_layouts(case):
         check(got, ref, BF16, "mid-size case %d decode sync=%d remote=%s" % (case, sync, rl is not None))
 
 
+def test_more_than_65535_query_tiles():
+    """2.1 million tokens in 128 ragged segments, bidirectional local block with 32-row query
+    tiles: 65 664 query tiles in one launch (tile indices beyond 16 bits)."""
+    N, seglen, Hq, Hkv, D = 128, 16400, 4, 1, 64
+    total = N * seglen
+    seg = (np.arange(N + 1) * seglen).astype(np.int32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(78)
+    q = torch.randn(total, Hq, D, generator=g, device="cuda", dtype=BF16)
+    k = torch.randn(total, Hkv, D, generator=g, device="cuda", dtype=BF16)
+    v = torch.randn(total, Hkv, D, generator=g, device="cuda", dtype=BF16)
+    out = torch.full_like(q, float("nan"))
+    p = fa.make_params(N, Hq, Hkv, D, 0, BF16, causal=False)
+    say("prefill local, bidirectional, 65664 query tiles")
+    fa.fedattn_prefill(p, 0, q, k, v, out, seg, sync_override=0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(10)
+    for n in (0, 64, 127):
+        sl = slice(int(seg[n]), int(seg[n + 1]))
+        rows = np.concatenate([[0, 31, 32, seglen - 17, seglen - 16, seglen - 1], rng.integers(0, seglen, size=18)]).astype(np.int32)
+        heads = rng.integers(0, Hq, size=rows.shape[0]).astype(np.int32)
+        ref = oracle.attend_rows(host(q[sl]), host(k[sl]), host(v[sl]), [0, seglen], rows, heads, is_sync=False, causal=False)
+        check(host(out[sl])[rows, heads], ref, BF16, "65664 query tiles, participant %d" % n)
+    assert bool(torch.isfinite(out.float()).all()), "rows never written"
+
+
 def test_offsets_beyond_32_bits():
     """One million tokens, 128 participants: byte offsets into q, k, v, out and the caches pass
     2^32 (q/out 8.6 GB, k/v 4.3 GB each).  Inputs of this size are drawn on the device; the
