@@ -31,14 +31,38 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   if (r >= rows) return;
   const f32x4* xr = reinterpret_cast<const f32x4*>(x + r * d_model);
   const int n4 = d_model / 4;
+  u32x2_t* orow = reinterpret_cast<u32x2_t*>(out + r * d_model);
   float ss = 0.f;
+  // rows of up to 4096 elements stay in registers between the two passes (16 vectors per lane)
+  constexpr int kHeld = 16;
+  if (n4 <= kHeld * 64) {
+    f32x4 held[kHeld];
+#pragma unroll
+    for (int j = 0; j < kHeld; ++j) {
+      const int i = lane + 64 * j;
+      held[j] = i < n4 ? xr[i] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int j = 0; j < kHeld; ++j) {
+      const f32x4 v = held[j];
+      ss += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+    }
+    ss = wave_sum(ss);
+    const float inv = 1.0f / sqrtf(ss / (float)d_model + eps);
+#pragma unroll
+    for (int j = 0; j < kHeld; ++j) {
+      const int i = lane + 64 * j;
+      const f32x4 v = held[j];
+      if (i < n4) orow[i] = u32x2_t{pack_bf16(v[0] * inv, v[1] * inv), pack_bf16(v[2] * inv, v[3] * inv)};
+    }
+    return;
+  }
   for (int i = lane; i < n4; i += 64) {
     const f32x4 v = xr[i];
     ss += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
   }
   ss = wave_sum(ss);
   const float inv = 1.0f / sqrtf(ss / (float)d_model + eps);
-  u32x2_t* orow = reinterpret_cast<u32x2_t*>(out + r * d_model);
   for (int i = lane; i < n4; i += 64) {
     const f32x4 v = xr[i];
     orow[i] = u32x2_t{pack_bf16(v[0] * inv, v[1] * inv), pack_bf16(v[2] * inv, v[3] * inv)};

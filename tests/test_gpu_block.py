@@ -30,7 +30,7 @@ def _bf16_close(got, ref_unrounded, what, slack=1.0):
 
 def test_rmsnorm_kernel():
     g = np.random.default_rng(1)
-    for rows, d in ((37, 2048), (5, 96), (1, 4)):
+    for rows, d in ((37, 2048), (5, 96), (1, 4), (6, 4096), (3, 4100), (2, 8192)):   # in registers up to 4096, two passes beyond
         x = (g.standard_normal((rows, d)) * 3).astype(np.float32)
         tx = torch.from_numpy(x).cuda()
         out = torch.full((rows, d), float("nan"), dtype=BF16, device="cuda")
