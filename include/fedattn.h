@@ -169,6 +169,25 @@ FEDATTN_API fedattn_status fedattn_decode_blocks(const fedattn_params* params, i
                                      size_t workspace_bytes, void* stream);
 
 /*
+ * fedattn_decode_blocks for callers that hold the queries of all n_blocks blocks before the
+ * first one runs (the blocks of a model do not: the query of block m + 1 comes out of block
+ * m; this entry point serves measurements of the kernels without launch effects and callers
+ * with independent layers): same arguments and results, but the blocks of one kind (local /
+ * sync, Algorithm 1) share launches.  Every block in flight works in its own slice of the
+ * workspace: a launch takes as many blocks as the workspace has slices of
+ * fedattn_workspace_bytes(DECODE) rounded up to 256 bytes (at least one, at most 64).
+ * No order is kept between the blocks; q, the caches and out of different blocks must not
+ * overlap.
+ */
+FEDATTN_API fedattn_status fedattn_decode_blocks_fused(const fedattn_params* params, int32_t block_idx0,
+                                           int32_t n_blocks, const void* q, const void* k_cache,
+                                           const void* v_cache, void* out, int64_t q_block_stride,
+                                           int64_t cache_block_stride, const int32_t* seg_offsets,
+                                           const int32_t* seg_lens, const int32_t* remote_lens,
+                                           int32_t sync_override, void* workspace, size_t workspace_bytes,
+                                           void* stream);
+
+/*
  * KV aggregation of a sync block (Phase II): [K V] = sum_n Pi_n [k_n v_n], i.e.
  * row r of participant n's local k_n, v_n lands at global row seg_offsets[n] + r.
  *   k_local,v_local host arrays of N device pointers, entry n -> [len_n,Hkv,D]

@@ -24,7 +24,8 @@ FEDATTN_OP_PREFILL, FEDATTN_OP_DECODE = 0, 1
 FEDATTN_MAX_PARTICIPANTS = 128
 
 EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill",
-           "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_aggregate_kv",
+           "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_decode_blocks_fused",
+           "fedattn_aggregate_kv",
            "fedattn_rmsnorm", "fedattn_rope_split_qkv", "fedattn_swiglu", "fedattn_residual_add",
            "fedattn_last_error", "fedattn_version")
 
@@ -68,6 +69,8 @@ def load():
     lib.fedattn_decode.restype = ctypes.c_int
     lib.fedattn_decode_blocks.argtypes = [pp, i32, i32, vp, vp, vp, vp, i64, i64, vp, vp, vp, i32, vp, sz, vp]
     lib.fedattn_decode_blocks.restype = ctypes.c_int
+    lib.fedattn_decode_blocks_fused.argtypes = lib.fedattn_decode_blocks.argtypes
+    lib.fedattn_decode_blocks_fused.restype = ctypes.c_int
     lib.fedattn_aggregate_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.fedattn_aggregate_kv.restype = ctypes.c_int
     fl = ctypes.c_float
@@ -186,7 +189,8 @@ def fedattn_decode(params: fedattn_params, block_idx: int, q: torch.Tensor, k_ca
 def fedattn_decode_blocks(params: fedattn_params, block_idx0: int, n_blocks: int, q: torch.Tensor,
                           k_cache: torch.Tensor, v_cache: torch.Tensor, out: torch.Tensor, q_block_stride: int,
                           cache_block_stride: int, seg_offsets, seg_lens, remote_lens=None, sync_override: int = -1,
-                          workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+                          workspace: Optional[torch.Tensor] = None, stream=None, fused: bool = False) -> None:
+    """fused=True calls fedattn_decode_blocks_fused (blocks of one kind share launches)."""
     seg = _host_i32(seg_offsets, "seg_offsets")
     lens = _host_i32(seg_lens, "seg_lens")
     if seg.shape[0] != params.n_participants + 1 or lens.shape[0] != params.n_participants:
@@ -197,13 +201,18 @@ def fedattn_decode_blocks(params: fedattn_params, block_idx0: int, n_blocks: int
         if rl.shape[0] != params.n_participants:
             raise ValueError("remote_lens has the wrong length")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load().fedattn_decode_blocks(ctypes.byref(params), int(block_idx0), int(n_blocks), _dev(q, "q"),
-                                        _dev(k_cache, "k_cache"), _dev(v_cache, "v_cache"), _dev(out, "out"),
-                                        int(q_block_stride), int(cache_block_stride),
-                                        seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
-                                        None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
-                                        int(sync_override), _dev(workspace, "workspace"), ws_bytes,
-                                        _stream(stream)))
+    fn = load().fedattn_decode_blocks_fused if fused else load().fedattn_decode_blocks
+    _check(fn(ctypes.byref(params), int(block_idx0), int(n_blocks), _dev(q, "q"),
+              _dev(k_cache, "k_cache"), _dev(v_cache, "v_cache"), _dev(out, "out"),
+              int(q_block_stride), int(cache_block_stride),
+              seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
+              None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
+              int(sync_override), _dev(workspace, "workspace"), ws_bytes, _stream(stream)))
+
+
+def fedattn_decode_blocks_fused(*args, **kwargs) -> None:
+    """Same arguments as fedattn_decode_blocks."""
+    fedattn_decode_blocks(*args, fused=True, **kwargs)
 
 
 def fedattn_aggregate_kv(params: fedattn_params, k_local: Sequence[Optional[torch.Tensor]],

@@ -274,12 +274,14 @@ fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t bloc
                      nullptr, 0, -1, nullptr, 0, stream);
 }
 
-fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
-                                     const void* q, const void* k_cache, const void* v_cache, void* out,
-                                     int64_t q_block_stride, int64_t cache_block_stride,
-                                     const int32_t* seg_offsets, const int32_t* seg_lens,
-                                     const int32_t* remote_lens, int32_t sync_override, void* workspace,
-                                     size_t workspace_bytes, void* stream) {
+// fused: blocks of one kind (local / sync) share launches, as many per launch as the workspace
+// has slices for; otherwise one launch (pair) per block in block order
+static fedattn_status run_decode(bool fused, const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                 const void* q, const void* k_cache, const void* v_cache, void* out,
+                                 int64_t q_block_stride, int64_t cache_block_stride,
+                                 const int32_t* seg_offsets, const int32_t* seg_lens,
+                                 const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
   fedattn_status st = check_params(params);
   if (st != FEDATTN_OK) return st;
   st = check_offsets(params, seg_offsets);
@@ -310,20 +312,32 @@ fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block
   DecodeArgs args[2];  // [0] local block, [1] sync block: the split differs, the layout does not
   bool built[2] = {false, false};
   int32_t* counters = nullptr;
+  int slices = 1;            // blocks in flight at once, each in its own slice of the workspace
+  size_t slice_bytes = 0;
   if (mfma) {
     const size_t need = decode_ws_bytes(params, capacity);
     if (!workspace || workspace_bytes < need)
       return fail(FEDATTN_EWORKSPACE, "decode needs %zu workspace bytes, got %zu", need, workspace_bytes);
     if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
-    // local blocks count their chunks in at the end of the workspace; the counters start at
+    slice_bytes = align_up(need, 256);
+    if (fused) {
+      if (n_blocks > 65535) return fail(FEDATTN_EINVAL, "at most 65535 blocks per fused call");
+      const size_t fit = 1 + (workspace_bytes - need) / slice_bytes;
+      slices = (int)(fit < (size_t)kMaxFusedBlocks ? fit : (size_t)kMaxFusedBlocks);
+      if (slices > n_blocks) slices = n_blocks;
+    }
+    // local blocks count their chunks in at the end of their slice; the counters start at
     // zero and every launch leaves them at zero for the next one
     counters = reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(workspace) + need - decode_counter_bytes(params));
-    hipError_t e = launch_decode_zero_counters(counters, params->n_kv_heads * N, reinterpret_cast<hipStream_t>(stream));
+    hipError_t e = launch_decode_zero_counters(counters, params->n_kv_heads * N, slices, (int64_t)slice_bytes,
+                                               reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (counters): %s", hipGetErrorString(e));
   }
-  for (int b = 0; b < n_blocks; ++b) {
-    const bool sync =
-        sync_override >= 0 ? sync_override != 0 : sync_block_rule(params->sync_interval, block_idx0 + b);
+  fused = fused && mfma;
+  const auto block_is_sync = [&](int b) {
+    return sync_override >= 0 ? sync_override != 0 : sync_block_rule(params->sync_interval, block_idx0 + b);
+  };
+  const auto prepare = [&](bool sync) -> fedattn_status {
     DecodeArgs& a = args[sync ? 1 : 0];
     if (!built[sync ? 1 : 0]) {
       memset(&a, 0, sizeof(a));
@@ -367,16 +381,70 @@ fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block
         for (int n = 0; n < N; ++n) all_have_rows = all_have_rows && seg_lens[n] > 0;
         a.fuse_combine = (!sync && a.cols <= 16 && all_have_rows) ? 1 : 0;
       }
+      a.q_block_bytes = q_block_stride * (int64_t)esize;
+      a.cache_block_bytes = cache_block_stride * (int64_t)esize;
+      a.slice_bytes = (int64_t)slice_bytes;
       built[sync ? 1 : 0] = true;
     }
+    return FEDATTN_OK;
+  };
+  if (fused) {
+    for (int kind = 0; kind < 2; ++kind) {
+      int first = 0;
+      while (first < n_blocks) {
+        int cnt = 0;
+        DecodeArgs& a = args[kind];
+        int b = first;
+        for (; b < n_blocks && cnt < slices; ++b) {
+          if ((block_is_sync(b) ? 1 : 0) != kind) continue;
+          if (cnt == 0) {
+            st = prepare(kind == 1);
+            if (st != FEDATTN_OK) return st;
+          }
+          a.block_list[cnt++] = (uint16_t)b;
+        }
+        first = b;
+        if (cnt == 0) continue;
+        a.q = q; a.out = out; a.k_cache = k_cache; a.v_cache = v_cache;
+        hipError_t e = launch_decode(a, params->dtype, cnt, reinterpret_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (fused, %d blocks): %s", cnt, hipGetErrorString(e));
+      }
+    }
+    return FEDATTN_OK;
+  }
+  for (int b = 0; b < n_blocks; ++b) {
+    const bool sync = block_is_sync(b);
+    st = prepare(sync);
+    if (st != FEDATTN_OK) return st;
+    DecodeArgs& a = args[sync ? 1 : 0];
     a.q = reinterpret_cast<const unsigned char*>(q) + (size_t)b * (size_t)q_block_stride * esize;
     a.out = reinterpret_cast<unsigned char*>(out) + (size_t)b * (size_t)q_block_stride * esize;
     a.k_cache = reinterpret_cast<const unsigned char*>(k_cache) + (size_t)b * (size_t)cache_block_stride * esize;
     a.v_cache = reinterpret_cast<const unsigned char*>(v_cache) + (size_t)b * (size_t)cache_block_stride * esize;
-    hipError_t e = launch_decode(a, params->dtype, reinterpret_cast<hipStream_t>(stream));
+    hipError_t e = launch_decode(a, params->dtype, 1, reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (block %d): %s", block_idx0 + b, hipGetErrorString(e));
   }
   return FEDATTN_OK;
+}
+
+fedattn_status fedattn_decode_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                     const void* q, const void* k_cache, const void* v_cache, void* out,
+                                     int64_t q_block_stride, int64_t cache_block_stride,
+                                     const int32_t* seg_offsets, const int32_t* seg_lens,
+                                     const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  return run_decode(false, params, block_idx0, n_blocks, q, k_cache, v_cache, out, q_block_stride, cache_block_stride,
+                    seg_offsets, seg_lens, remote_lens, sync_override, workspace, workspace_bytes, stream);
+}
+
+fedattn_status fedattn_decode_blocks_fused(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                           const void* q, const void* k_cache, const void* v_cache, void* out,
+                                           int64_t q_block_stride, int64_t cache_block_stride,
+                                           const int32_t* seg_offsets, const int32_t* seg_lens,
+                                           const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  return run_decode(true, params, block_idx0, n_blocks, q, k_cache, v_cache, out, q_block_stride, cache_block_stride,
+                    seg_offsets, seg_lens, remote_lens, sync_override, workspace, workspace_bytes, stream);
 }
 
 fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, const void* q, const void* k_cache,

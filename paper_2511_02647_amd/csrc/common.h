@@ -12,7 +12,8 @@ namespace fedattn {
 constexpr int kMaxP = FEDATTN_MAX_PARTICIPANTS;
 constexpr int kKvTile = 64;    // KV rows per MFMA prefill tile; also the keep-list tile
 constexpr int kWaveRows = 32;  // query rows per wave in the MFMA prefill kernel
-constexpr int kMaxOrderedTiles = 512;  // query tiles of a launch that assigns them through an explicit order
+constexpr int kMaxOrderedTiles = 512;
+constexpr int kMaxFusedBlocks = 64;    // blocks of one fused decode launch  // query tiles of a launch that assigns them through an explicit order
 
 // Segment layout of the global sequence, passed by value in the kernel arguments
 // (read with scalar loads; no device copy of host arrays is needed).
@@ -71,6 +72,13 @@ struct DecodeArgs {
   int32_t cols;             // query columns per partial row block: G (local) or N*G (sync)
   int32_t has_remote;       // remote_lens given
   float scale;
+  // several blocks in one launch (grid z, or y for the combine): block z is block_list[z]
+  // blocks of block_stride bytes away from q/out and the caches, and works in its own slice
+  // of the workspace (slice_bytes apart, partials and counters laid out alike in every slice)
+  int64_t q_block_bytes;
+  int64_t cache_block_bytes;
+  int64_t slice_bytes;
+  uint16_t block_list[kMaxFusedBlocks];
   int32_t seg_off[kMaxP + 1];
   int32_t seg_lens[kMaxP];
   int32_t remote_lens[kMaxP];
@@ -94,8 +102,8 @@ hipError_t launch_build_kept_tiles(const PrefillArgs& a, int2* kept_tiles, int32
                                    hipStream_t s);
 hipError_t launch_pack_kept_rows(const PrefillArgs& a, int32_t* kept_rows, int32_t* src_index, void* k_packed,
                                  void* v_packed, int2* kept_tiles, int32_t* kept_cum, hipStream_t s);
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
-hipError_t launch_decode_zero_counters(int32_t* counters, int n, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs& a, int dtype, int n_z, hipStream_t s);
+hipError_t launch_decode_zero_counters(int32_t* counters, int n, int slices, int64_t slice_bytes, hipStream_t s);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t s);
 hipError_t launch_rmsnorm(const float* x, void* out, int64_t rows, int d_model, float eps, hipStream_t s);
 hipError_t launch_rope_split(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens, int Hq,

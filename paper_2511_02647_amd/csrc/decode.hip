@@ -72,6 +72,17 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
   const int l16 = lane & 15;
   const int kg = lane >> 4;
 
+  // block of a fused launch: its q/out, caches and workspace slice
+  const int bz = blockIdx.z;
+  const int64_t blk = a.block_list[bz];
+  const unsigned char* q_ptr = reinterpret_cast<const unsigned char*>(a.q) + blk * a.q_block_bytes;
+  unsigned char* out_ptr = reinterpret_cast<unsigned char*>(a.out) + blk * a.q_block_bytes;
+  const unsigned char* k_ptr = reinterpret_cast<const unsigned char*>(a.k_cache) + blk * a.cache_block_bytes;
+  const unsigned char* v_ptr = reinterpret_cast<const unsigned char*>(a.v_cache) + blk * a.cache_block_bytes;
+  float* part_o = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(a.part_o) + bz * a.slice_bytes);
+  float* part_ml = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(a.part_ml) + bz * a.slice_bytes);
+  int32_t* counters = reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(a.counters) + bz * a.slice_bytes);
+
   const int Hq = a.Hq, Hkv = a.Hkv;
   const int G = Hq / Hkv;
   const int g = blockIdx.x % Hkv;
@@ -107,8 +118,8 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
   const int nt = (r_hi - r_lo + kKvTile - 1) / kKvTile;
   const int row_elems = Hkv * D;
 
-  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(a.k_cache) + ((int64_t)(seg_row0 + r_lo) * Hkv + g) * D;
-  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(a.v_cache) + ((int64_t)(seg_row0 + r_lo) * Hkv + g) * D;
+  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(k_ptr) + ((int64_t)(seg_row0 + r_lo) * Hkv + g) * D;
+  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(v_ptr) + ((int64_t)(seg_row0 + r_lo) * Hkv + g) * D;
 
   TL tile_io;
   tile_io.init(lane, wave, row_elems);
@@ -126,7 +137,7 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
   const int limit = col_ok ? (col_part == m ? own_len : rem_len) : 0;  // visible rows of this segment
   u32x4 qw[KS];  // B operand of S^T: Q[col][32 st + 8 kg .. +8]
   {
-    const uint16_t* qrow = reinterpret_cast<const uint16_t*>(a.q) + ((int64_t)col_part * Hq + col_head) * D + 8 * kg;
+    const uint16_t* qrow = reinterpret_cast<const uint16_t*>(q_ptr) + ((int64_t)col_part * Hq + col_head) * D + 8 * kg;
 #pragma unroll
     for (int st = 0; st < KS; ++st)
       asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qw[st]) : "v"(qrow + 32 * st) : "memory");
@@ -285,10 +296,10 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
     if (rh == 0 && col_ok) {
       const int64_t prow = ((int64_t)g * a.n_chunks + gc) * a.cols + col;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(a.part_o + prow * D + 16 * dt + 4 * kg) = o[dt];
+      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<f32x4*>(part_o + prow * D + 16 * dt + 4 * kg) = o[dt];
       if (kg == 0) {
-        a.part_ml[prow * 2] = m_run;
-        a.part_ml[prow * 2 + 1] = l_run;
+        part_ml[prow * 2] = m_run;
+        part_ml[prow * 2 + 1] = l_run;
       }
     }
   } else {
@@ -308,7 +319,7 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
     const int64_t prow0 = ((int64_t)g * a.n_chunks + gc) * a.cols + col0;
     const float* o_all = reinterpret_cast<const float*>(smem);
     // local block with the combine fused in: query column cl is head g G + cl of participant m
-    uint16_t* out_rows = reinterpret_cast<uint16_t*>(a.out) + ((int64_t)m * Hq + g * G + col0) * D;
+    uint16_t* out_rows = reinterpret_cast<uint16_t*>(out_ptr) + ((int64_t)m * Hq + g * G + col0) * D;
     if (a.fuse_combine && n_seg_chunks == 1) {
       // the segment's only chunk: normalise and write the output rows, no partials
       for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
@@ -333,11 +344,11 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
         const f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 16 * OPAD);
         const f32x4 v2 = *reinterpret_cast<const f32x4*>(src + 32 * OPAD);
         const f32x4 v3 = *reinterpret_cast<const f32x4*>(src + 48 * OPAD);
-        *reinterpret_cast<f32x4*>(a.part_o + (prow0 + cl) * D + 4 * d4) = (v0 + v1) + (v2 + v3);
+        *reinterpret_cast<f32x4*>(part_o + (prow0 + cl) * D + 4 * d4) = (v0 + v1) + (v2 + v3);
       }
       if (tid < n_cols) {
-        a.part_ml[(prow0 + tid) * 2] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
-        a.part_ml[(prow0 + tid) * 2 + 1] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
+        part_ml[(prow0 + tid) * 2] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
+        part_ml[(prow0 + tid) * 2 + 1] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
       }
       return;
     }
@@ -358,15 +369,15 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
       const f32x4 v2 = *reinterpret_cast<const f32x4*>(src + 32 * OPAD);
       const f32x4 v3 = *reinterpret_cast<const f32x4*>(src + 48 * OPAD);
       const f32x4 sum = (v0 + v1) + (v2 + v3);
-      float* dst = a.part_o + (prow0 + cl) * D + 4 * d4;
+      float* dst = part_o + (prow0 + cl) * D + 4 * d4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) __hip_atomic_store(dst + e, sum[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tid < n_cols) {
-      __hip_atomic_store(a.part_ml + (prow0 + tid) * 2,
+      __hip_atomic_store(part_ml + (prow0 + tid) * 2,
                          fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid])), __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(a.part_ml + (prow0 + tid) * 2 + 1, l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid],
+      __hip_atomic_store(part_ml + (prow0 + tid) * 2 + 1, l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid],
                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __shared__ int last_s;
@@ -375,7 +386,7 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
     __syncthreads();
     if (tid == 0) {
-      int* cnt = a.counters + g * N + m;  // at most 16 columns: one workgroup per chunk
+      int* cnt = counters + g * N + m;  // at most 16 columns: one workgroup per chunk
       const int seen = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const int last = seen == n_seg_chunks - 1;
       if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -387,14 +398,14 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
     const int64_t cstride = a.cols;                                            // partial rows between chunks
     for (int idx = tid; idx < n_cols * (D / 4); idx += 256) {
       const int cl = idx / (D / 4), d4 = idx % (D / 4);
-      const float* ml = a.part_ml + (crow0 + cl) * 2;
+      const float* ml = part_ml + (crow0 + cl) * 2;
       float mm = -INFINITY;
       for (int cc = 0; cc < n_seg_chunks; ++cc)
         mm = fmaxf(mm, __hip_atomic_load(ml + cc * cstride * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
       const float mu = (mm == -INFINITY) ? 0.f : mm;
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
       float den = 0.f;
-      const float* po = a.part_o + (crow0 + cl) * D + 4 * d4;
+      const float* po = part_o + (crow0 + cl) * D + 4 * d4;
       for (int cc = 0; cc < n_seg_chunks; ++cc) {
         const float mc = __hip_atomic_load(ml + cc * cstride * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const float lc = __hip_atomic_load(ml + cc * cstride * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -413,9 +424,9 @@ __global__ __launch_bounds__(COLSPLIT ? 512 : 256, 1) void decode_stream_kernel(
 
 // Zeroes the chunk counters of the fused combine (a kernel rather than a memset so that
 // callers may capture the calls in a graph).
-__global__ void decode_zero_counters_kernel(int32_t* counters, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) counters[i] = 0;
+__global__ void decode_zero_counters_kernel(int32_t* counters, int n, int64_t slice_bytes) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;  // grid y: workspace slice
+  if (i < n) reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(counters) + blockIdx.y * slice_bytes)[i] = 0;
 }
 
 // Merges the chunk partials of one (participant, query head) and writes the output row:
@@ -441,13 +452,18 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
   const int tid = threadIdx.x;
   const int D = a.D, D4 = D / 4;
   const int d4 = tid % D4, cg = tid / D4;  // blockDim = D4 * CG
+  // block of a fused launch
+  const int bz = blockIdx.y;
+  unsigned char* out_ptr = reinterpret_cast<unsigned char*>(a.out) + (int64_t)a.block_list[bz] * a.q_block_bytes;
+  const float* part_o = reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(a.part_o) + bz * a.slice_bytes);
+  const float* part_ml = reinterpret_cast<const float*>(reinterpret_cast<const unsigned char*>(a.part_ml) + bz * a.slice_bytes);
   const int64_t cstride = a.cols;          // partial rows between consecutive chunks
 
   if (c1 - c0 <= 16 * CG) {
     // Few chunks (the usual case): one round trip.  Every thread requests its partial O rows
     // and one chunk's (m, l) before anything is known about the weights.
     const int nb = c1 - c0;
-    const float* po = a.part_o + ((base + c0) * cstride + col) * D + 4 * d4;
+    const float* po = part_o + ((base + c0) * cstride + col) * D + 4 * d4;
     f32x4 part[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
@@ -456,7 +472,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
     }
     float m_i = -INFINITY, l_i = 0.f;
     if (tid < nb) {
-      const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + ((base + c0 + tid) * cstride + col) * 2);
+      const f32x2 ml = *reinterpret_cast<const f32x2*>(part_ml + ((base + c0 + tid) * cstride + col) * 2);
       m_i = ml[0];
       l_i = ml[1];
     }
@@ -488,7 +504,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
       const float dn = m_s[8];
       const f32x4 sum = (acc_s[0][d4] + acc_s[1][d4]) + (acc_s[2][d4] + acc_s[3][d4]);
       const f32x4 val = sum * (dn > 0.f ? 1.f / dn : 0.f);
-      T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * D + 4 * d4;
+      T* out = reinterpret_cast<T*>(out_ptr) + ((int64_t)n * a.Hq + h) * D + 4 * d4;
       if constexpr (sizeof(T) == 2) {
         const bf16x4 w4 = {(bf16_t)val[0], (bf16_t)val[1], (bf16_t)val[2], (bf16_t)val[3]};
         *reinterpret_cast<u32x2*>(out) = __builtin_bit_cast(u32x2, w4);
@@ -501,7 +517,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
 
   // row maximum over all chunks
   float mm = -INFINITY;
-  for (int cc = c0 + tid; cc < c1; cc += blockDim.x) mm = fmaxf(mm, a.part_ml[((base + cc) * cstride + col) * 2]);
+  for (int cc = c0 + tid; cc < c1; cc += blockDim.x) mm = fmaxf(mm, part_ml[((base + cc) * cstride + col) * 2]);
   mm = wave_max(mm);
   if ((tid & 63) == 0) m_s[tid >> 6] = mm;
   __syncthreads();
@@ -515,12 +531,12 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
     const int nb = min(256, c1 - cb);
     __syncthreads();
     for (int i = tid; i < nb; i += blockDim.x) {
-      const float* ml = a.part_ml + ((base + cb + i) * cstride + col) * 2;
+      const float* ml = part_ml + ((base + cb + i) * cstride + col) * 2;
       w_s[i] = __builtin_amdgcn_exp2f(ml[0] - mu);
       l_s[i] = ml[1];
     }
     __syncthreads();
-    const float* po = a.part_o + ((base + cb) * cstride + col) * D + 4 * d4;
+    const float* po = part_o + ((base + cb) * cstride + col) * D + 4 * d4;
 #pragma unroll 8
     for (int i = cg; i < nb; i += CG) acc += *reinterpret_cast<const f32x4*>(po + i * cstride * D) * w_s[i];
     if (tid == 0)
@@ -533,7 +549,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a) {
     const float dn = m_s[8];
     const f32x4 sum = (acc_s[0][d4] + acc_s[1][d4]) + (acc_s[2][d4] + acc_s[3][d4]);
     const f32x4 val = sum * (dn > 0.f ? 1.f / dn : 0.f);
-    T* out = reinterpret_cast<T*>(a.out) + ((int64_t)n * a.Hq + h) * D + 4 * d4;
+    T* out = reinterpret_cast<T*>(out_ptr) + ((int64_t)n * a.Hq + h) * D + 4 * d4;
     if constexpr (sizeof(T) == 2) {
       const bf16x4 w4 = {(bf16_t)val[0], (bf16_t)val[1], (bf16_t)val[2], (bf16_t)val[3]};
       *reinterpret_cast<u32x2*>(out) = __builtin_bit_cast(u32x2, w4);
@@ -620,7 +636,7 @@ __global__ __launch_bounds__(64) void decode_rows_kernel(DecodeArgs a) {
 }
 
 template <int D, bool COLSPLIT>
-hipError_t launch_stream_mode(const DecodeArgs& a, hipStream_t s) {
+hipError_t launch_stream_mode(const DecodeArgs& a, int n_z, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, COLSPLIT>),
@@ -629,22 +645,24 @@ hipError_t launch_stream_mode(const DecodeArgs& a, hipStream_t s) {
     attr_set = true;
   }
   const int qcols = COLSPLIT ? 64 : 16;
-  dim3 grid((unsigned)(a.n_chunks * a.Hkv), (unsigned)((a.cols + qcols - 1) / qcols), 1);
+  dim3 grid((unsigned)(a.n_chunks * a.Hkv), (unsigned)((a.cols + qcols - 1) / qcols), (unsigned)n_z);
   hipLaunchKernelGGL((decode_stream_kernel<D, COLSPLIT>), grid, dim3(COLSPLIT ? 512 : 256), decode_smem_bytes<D>(), s, a);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_stream(const DecodeArgs& a, hipStream_t s) {
-  return a.cols <= 16 ? launch_stream_mode<D, false>(a, s) : launch_stream_mode<D, true>(a, s);
+hipError_t launch_stream(const DecodeArgs& a, int n_z, hipStream_t s) {
+  return a.cols <= 16 ? launch_stream_mode<D, false>(a, n_z, s) : launch_stream_mode<D, true>(a, n_z, s);
 }
 
 }  // namespace
 
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
-  if (a.N == 0) return hipSuccess;
+// n_z > 1: the blocks a.block_list[0 .. n_z) in one launch (MFMA path only)
+hipError_t launch_decode(const DecodeArgs& a, int dtype, int n_z, hipStream_t s) {
+  if (a.N == 0 || n_z == 0) return hipSuccess;
   const bool mfma = dtype == FEDATTN_BF16 && (a.D == 64 || a.D == 128);
   if (!mfma) {
+    if (n_z != 1) return hipErrorInvalidValue;
     dim3 grid((unsigned)(a.N * a.Hq));
     if (dtype == FEDATTN_F32)
       hipLaunchKernelGGL(decode_rows_kernel<float>, grid, dim3(64), 0, s, a);
@@ -653,17 +671,18 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
     return hipGetLastError();
   }
   if (a.n_chunks > 0) {
-    hipError_t e = a.D == 128 ? launch_stream<128>(a, s) : launch_stream<64>(a, s);
+    hipError_t e = a.D == 128 ? launch_stream<128>(a, n_z, s) : launch_stream<64>(a, n_z, s);
     if (e != hipSuccess) return e;
   }
   if (a.fuse_combine) return hipSuccess;
-  hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq)), dim3(a.D), 0,
+  hipLaunchKernelGGL(decode_combine_kernel<uint16_t>, dim3((unsigned)(a.N * a.Hq), (unsigned)n_z), dim3(a.D), 0,
                      s, a);
   return hipGetLastError();
 }
 
-hipError_t launch_decode_zero_counters(int32_t* counters, int n, hipStream_t s) {
-  hipLaunchKernelGGL(decode_zero_counters_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, counters, n);
+hipError_t launch_decode_zero_counters(int32_t* counters, int n, int slices, int64_t slice_bytes, hipStream_t s) {
+  hipLaunchKernelGGL(decode_zero_counters_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)slices), dim3(256), 0, s,
+                     counters, n, slice_bytes);
   return hipGetLastError();
 }
 

@@ -567,6 +567,40 @@ def test_decode_blocks_equals_per_block_calls():
         check(host(out[b]), ref, BF16, "decode_blocks block %d" % b)
 
 
+@pytest.mark.parametrize("lens", [[200, 150, 1, 77], [130, 0, 64, 200]])
+def test_decode_blocks_fused_equals_decode_blocks(lens):
+    """Blocks of one kind sharing launches (every block in flight in its own workspace slice):
+    bit-equal to one launch per block, whatever the number of slices the workspace holds; with
+    and without empty caches (chunks merged in the streaming kernel / by the combine kernel)."""
+    N, Hq, Hkv, D, cap, M, H = 4, 8, 2, 128, 200, 9, 4
+    seg = (np.arange(N + 1) * cap).astype(np.int32)
+    lens = np.array(lens, dtype=np.int32)
+    g = np.random.default_rng(22)
+    mk = lambda *s: fi.round_to_bf16(g.standard_normal(s).astype(np.float32))
+    q, kc, vc = mk(M, N, Hq, D), mk(M, N * cap, Hkv, D), mk(M, N * cap, Hkv, D)
+    tq, tk, tv = dev(q, BF16), dev(kc, BF16), dev(vc, BF16)
+    p = fa.make_params(N, Hq, Hkv, D, H, BF16)
+    one = fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, N * cap)
+    slice_bytes = (one + 255) // 256 * 256
+    ws1 = torch.empty(one, dtype=torch.uint8, device="cuda")
+    prompt = np.minimum(lens, 100).astype(np.int32)
+    for override, rl in [(-1, None), (-1, prompt), (0, None), (1, None)]:
+        ref = torch.full_like(tq, float("nan"))
+        fa.fedattn_decode_blocks(p, 0, M, tq, tk, tv, ref, tq[0].numel(), tk[0].numel(), seg, lens, remote_lens=rl,
+                                 sync_override=override, workspace=ws1)
+        torch.cuda.synchronize()
+        for n_slices in (1, 3, 9):
+            ws = torch.full((one + (n_slices - 1) * slice_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+            out = torch.full_like(tq, float("nan"))
+            say("decode_blocks_fused lens=%s override=%d remote=%s slices=%d" % (lens.tolist(), override, rl is not None, n_slices))
+            fa.fedattn_decode_blocks_fused(p, 0, M, tq, tk, tv, out, tq[0].numel(), tk[0].numel(), seg, lens,
+                                           remote_lens=rl, sync_override=override, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref), "fused decode differs (override %d, %d slices)" % (override, n_slices)
+    b = 3
+    check(host(ref[b]), oracle.decode_step(q[b], kc[b], vc[b], seg, lens, is_sync=True), BF16, "decode block 3 (forced sync)")
+
+
 # ------------------------------------------------------------------ aggregate
 def test_hip_graph_replays_match_eager():
     """A sequence of the library's launches (aggregate, local and sync prefill, sparse prefill with
