@@ -346,7 +346,9 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
         const int r = kk * RPI + lane / CPR;
         const u32x4 w = *reinterpret_cast<const u32x4*>(stage + r * ROWO + ((c ^ (r & (CPR - 1))) << 4));
         if (cur.row0w + r < cur.seg_hi)
-          *reinterpret_cast<u32x4*>(op + ((int64_t)(cur.row0w + r) * Hq + head) * D + 8 * c) = w;
+          // streaming store: the rows are not read again in this launch, and written through
+          // now they are not left for the write-back at the end of the kernel
+          __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(op + ((int64_t)(cur.row0w + r) * Hq + head) * D + 8 * c));
       }
     }
     if (!more) break;
