@@ -204,13 +204,40 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
       qf[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + 16 * st));
   };
 
+  // The first walk's Q rows come through LDS instead: loaded as above, an instruction touches
+  // 32 rows (32 bytes of each) and a launch of a few thousand tokens spends its first
+  // microsecond in the address path.  Here the wavefront moves its 32 x D tile with whole-row
+  // direct-to-LDS loads (4 rows of 2 D bytes per instruction) into the half of a K or V stage
+  // that the first tile does not use, in the K tile's swizzled layout, and reads the fragments
+  // back like K fragments.  Nobody else touches that half before the barrier below.
+  constexpr int QINST = kWaveRows * TL::ROWB / 1024;  // load instructions per wavefront
+  const int q_lds = (wave >> 1) * 2 * TILEB + TILEB + (wave & 1) * (TILEB / 2);  // byte offset in the group's stages
+  auto fetch_q_lds = [&](const Walk& w) __attribute__((always_inline)) {
+    const int rbase = min(w.row0w, w.seg_hi - 1);
+    const uint16_t* qbase = qp + ((int64_t)rbase * Hq + head) * D;
+#pragma unroll
+    for (int i = 0; i < QINST; ++i) {
+      const int sidx = i * 64 + lane;
+      const int row = sidx / TL::CPR, cp = sidx % TL::CPR;
+      const int row_ld = min(w.row0w + row, w.seg_hi - 1) - rbase;  // >= 0
+      const uint32_t off = (uint32_t)(row_ld * (Hq * D) + ((cp ^ (row & (TL::CPR - 1))) * 8)) * 2u;
+      lds_dma_16(qbase, off, lds_base + q_lds + i * 1024);
+    }
+  };
+  auto read_q_lds = [&](bf16x8 (&qf)[KSTEPS]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int st = 0; st < KSTEPS; ++st)
+      qf[st] = __builtin_bit_cast(
+          bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(lds0 + (q_lds + tile_io.k_off[st])));
+  };
+
   // The workgroup's walks run as one pipeline: the stage parity carries on from the
   // first walk into the second, whose first tile and Q fragments are fetched while
   // the first walk finishes.
   Walk cur, nxt;
   make_walk(tile_a, cur);
   bf16x8 qf[KSTEPS];
-  load_q(cur, qf);
+  fetch_q_lds(cur);
   if (grp < cur.nt) fetch_tile(cur, grp, 0);
   nxt = cur;
   const bool two = tile_b >= 0;
@@ -236,7 +263,10 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
 
     const int n_it = (cur.nt + NG - 1) / NG;  // iterations of the workgroup (uniform: they carry barriers)
     wait_vmcnt<0>();
-    if (part == 0) asm volatile("" ::"v"(warm));
+    if (part == 0) {
+      asm volatile("" ::"v"(warm));
+      read_q_lds(qf);  // this wavefront's own loads: landed with the wait above; the barrier waits for the reads
+    }
     __syncthreads();
 
     // ---- main loop: the group's i-th tile is computed from one stage while its next tile
