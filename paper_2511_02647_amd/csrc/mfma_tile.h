@@ -34,14 +34,26 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units a row maximum may lag be
 // lds_addr must be wave-uniform.  The instruction is written out so that the compiler
 // does not serialise it against unrelated LDS reads; completion is awaited explicitly
 // (vmcnt) before the barrier that publishes the tile.
+// STREAM: nontemporal hint, for rows that are read once (they then pass the caches without
+// displacing anything).
+template <bool STREAM = false>
 __device__ inline void lds_dma_16(const void* base, uint32_t off, uint32_t lds_addr) {
-  asm volatile(
-      "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2"
-      :
-      : "s"(lds_addr), "v"(off), "s"(base)
-      : "memory", "m0");
+  if constexpr (STREAM)
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2 nt"
+        :
+        : "s"(lds_addr), "v"(off), "s"(base)
+        : "memory", "m0");
+  else
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2"
+        :
+        : "s"(lds_addr), "v"(off), "s"(base)
+        : "memory", "m0");
 }
 
 __device__ inline uint32_t lds_addr_of(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
@@ -139,18 +151,18 @@ struct KvTile {
   // This wavefront's share of one tile: `tile_base` points at the tile's first row
   // (wave-uniform), `lds_stage` is the LDS byte address of the stage.  Rows past the
   // tile's valid length re-read its last valid row (they are masked out of the scores).
-  template <bool IS_V>
+  template <bool IS_V, bool STREAM = false>
   __device__ __attribute__((always_inline)) void dma(const uint16_t* tile_base, uint32_t lds_stage, int len) const {
     if (len == kKvTile) {
 #pragma unroll
       for (int i = 0; i < IPW; ++i)
-        lds_dma_16(tile_base, IS_V ? dma_voff[i] : dma_koff[i], lds_stage + (wave * IPW + i) * 1024);
+        lds_dma_16<STREAM>(tile_base, IS_V ? dma_voff[i] : dma_koff[i], lds_stage + (wave * IPW + i) * 1024);
     } else {
 #pragma unroll
       for (int i = 0; i < IPW; ++i) {
         const uint32_t o2 =
             (uint32_t)(min(dma_row[i], len - 1) * row_elems + (IS_V ? dma_vcol[i] : dma_kcol[i])) * 2u;
-        lds_dma_16(tile_base, o2, lds_stage + (wave * IPW + i) * 1024);
+        lds_dma_16<STREAM>(tile_base, o2, lds_stage + (wave * IPW + i) * 1024);
       }
     }
   }
