@@ -62,3 +62,23 @@ def test_validation_returns_codes_without_touching_the_gpu(lib):
     assert fa.fedattn_workspace_bytes(ok, fa.FEDATTN_OP_PREFILL, 4096, 0) == 0
     assert fa.fedattn_workspace_bytes(ok, fa.FEDATTN_OP_PREFILL, 4096, 64) > 0
     assert fa.fedattn_workspace_bytes(ok, fa.FEDATTN_OP_DECODE, 4096) > 0
+
+
+def test_decode_validation_returns_codes_without_touching_the_gpu(lib):
+    ok = fa.make_params(2, 4, 2, 128, 2, torch.bfloat16)
+    seg = (ctypes.c_int32 * 3)(0, 64, 128)
+    lens = (ctypes.c_int32 * 2)(64, 10)
+    null = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(0x10000)      # never dereferenced: every call below fails validation first
+    for fn in (lib.fedattn_decode_blocks, lib.fedattn_decode_blocks_fused):
+        assert fn(ctypes.byref(ok), 0, 2, fake, fake, fake, fake, 1024, 32768, seg, null, null, -1, null, 0, null) == fa.FEDATTN_EINVAL
+        assert fn(ctypes.byref(ok), 0, 0, null, null, null, null, 0, 0, seg, lens, null, -1, null, 0, null) == fa.FEDATTN_OK
+        bad = (ctypes.c_int32 * 2)(65, 10)   # more valid rows than the segment's capacity
+        assert fn(ctypes.byref(ok), 0, 2, fake, fake, fake, fake, 1024, 32768, seg, bad, null, -1, null, 0, null) == fa.FEDATTN_EINVAL
+        assert fn(ctypes.byref(ok), 0, 2, fake, fake, fake, fake, 1024, 32768, seg, lens, null, 2, null, 0, null) == fa.FEDATTN_EINVAL
+        assert fn(ctypes.byref(ok), 0, 2, fake, fake, fake, fake, 1023, 32768, seg, lens, null, -1, null, 0, null) == fa.FEDATTN_EINVAL
+        assert fn(ctypes.byref(ok), 0, 2, fake, fake, fake, fake, 1024, 32768, seg, lens, null, -1, null, 0, null) == fa.FEDATTN_EWORKSPACE
+    big = fa.fedattn_workspace_bytes(ok, fa.FEDATTN_OP_DECODE, 128)
+    assert lib.fedattn_decode_blocks_fused(ctypes.byref(ok), 0, 70000, fake, fake, fake, fake, 1024, 32768, seg, lens, null,
+                                           -1, fake, big, null) == fa.FEDATTN_EINVAL
+    assert b"65535" in lib.fedattn_last_error()
