@@ -165,7 +165,7 @@ class PrefillBench:
         """Average duration of the prefill kernel per block kind, HIP events around each launch."""
         evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                 for _ in range(self.M)] for _ in range(steps)]
-        torch.cuda.synchronize()
+        device_warmup(self.step)
         # keep the GPU busy while the host enqueues: the launches then run back to back and an
         # event pair brackets the kernel, not the time the GPU waited for the host
         if self.nd == self.M and self.keep is None:
@@ -230,8 +230,7 @@ class DecodeBench:
     def timed(self, steps, sync_override: int = -1, fused: bool = False) -> float:
         """GPU milliseconds for the given decode steps (HIP events around the whole run)."""
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        self.run_step(steps[0], sync_override, fused)
-        torch.cuda.synchronize()
+        device_warmup(lambda: self.run_step(steps[0], sync_override, fused))
         e0.record()
         for s in steps:
             self.run_step(s, sync_override, fused)
@@ -278,7 +277,22 @@ def end_to_end_leg(steps: int) -> dict:
             "tflops_all": (fl_attn + fl_gemm) / sec / 1e12, "finite": bool(torch.isfinite(x).all().item())}
 
 
+DEVICE_WARMUP_S = 0.3
+
+
+def device_warmup(fn, seconds: float = DEVICE_WARMUP_S) -> None:
+    """Untimed work before a measurement: the GPU raises its clock over the first tenths of a
+    second of sustained load (the headline step measured 0.90 ms right after idle and 0.84 ms
+    from 0.2 s on), and a throughput figure should be the sustained one."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
+
+
 def time_region(fn, steps: int, warmup: int) -> float:
+    device_warmup(fn)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -352,8 +366,8 @@ def cpu_baseline(pb: PrefillBench, budget_s: float = 12.0) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2_llama8b_prefill",
                     choices=["cfg2_llama8b_prefill", "cfg3_hetero_prefill", "cfg5_sparse_sync"])
     ap.add_argument("--sync-interval", type=int, default=None, help="override H of the workload")
@@ -431,7 +445,8 @@ def main() -> int:
                          "launch": ("one fedattn_prefill per block, fedattn_aggregate_kv before each sync block"
                                     if pb.aggregate else "one fedattn_prefill per block")
                                    + ("" if args.no_graph else "; the step's launches replayed from a HIP graph"),
-                         "ms_per_step_launched_from_python": sec_eager * 1e3},
+                         "ms_per_step_launched_from_python": sec_eager * 1e3,
+                         "untimed_device_warmup_s": DEVICE_WARMUP_S},
               "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS,
               "roofline": roof,
               "analytic_cost_per_participant": cost.as_dict()}
@@ -445,9 +460,7 @@ def main() -> int:
     if not args.no_decode:
         db = DecodeBench()
         steps = sorted(set(int(s) for s in np.linspace(0, db.w.decode_steps - 1, args.decode_steps)))
-        for s in steps[:2]:
-            db.run_step(s)
-        torch.cuda.synchronize()
+        device_warmup(lambda: db.run_step(steps[0]))
         t0 = time.perf_counter()
         for s in steps:
             db.run_step(s)
