@@ -50,6 +50,7 @@ struct PrefillArgs {
   int32_t n_cus;            // compute units of the device (launch shape heuristics)
   float scale;              // softmax scale
   int32_t n_ordered;        // > 0: one workgroup per query tile, workgroup p takes tile_order[p] (MFMA kernel)
+  int32_t warm_kv;          // MFMA kernel: every workgroup pulls the K, V rows of its own query rows into L2 first
   SegLayout seg;
   uint16_t tile_order[kMaxOrderedTiles];
 };

@@ -248,6 +248,24 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     const int row_ld = min(nxt.row0w + l32, nxt.seg_hi - 1);
     warm = *reinterpret_cast<const unsigned*>(qp + ((int64_t)row_ld * Hq + head) * D + (hf * 64) % D);
   }
+  // Small problems (all of a KV head's K and V fit in L2 with room to spare): the launch starts
+  // with every workgroup asking HBM for its Q rows and first tile at once, and the later tiles
+  // of the long walks would each be one more cold miss behind that burst.  Instead the K and V
+  // rows of the workgroup's own query rows are requested now, one dword per 128-byte line; all
+  // workgroups together cover every row, and the walks then find their tiles in L2.
+  unsigned warm_k = 0;
+  if (a.warm_kv && grp == 0) {
+    constexpr int LPR = TL::ROWB / 128;  // 128-byte lines per K/V row
+    const int sub = wave % HS;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (i % HS != sub || (i >= 2 && !two)) continue;   // wave-uniform
+      const Walk& w = i >= 2 ? nxt : cur;
+      const int row = min(w.row0w + lane / LPR, w.seg_hi - 1);
+      const uint16_t* base = (i & 1) ? vp : kp;
+      warm_k += *reinterpret_cast<const unsigned*>(base + (int64_t)row * row_elems + (lane % LPR) * 64);
+    }
+  }
   int git = 0;  // iterations this workgroup has run: stage of an iteration = git & 1
 
   for (int part = 0;; ++part) {
@@ -264,7 +282,7 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     const int n_it = (cur.nt + NG - 1) / NG;  // iterations of the workgroup (uniform: they carry barriers)
     wait_vmcnt<0>();
     if (part == 0) {
-      asm volatile("" ::"v"(warm));
+      asm volatile("" ::"v"(warm), "v"(warm_k));
       read_q_lds(qf);  // this wavefront's own loads: landed with the wait above; the barrier waits for the reads
     }
     __syncthreads();
@@ -546,6 +564,8 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a_in, int n_blocks, hipStream_
   if (a_in.n_q_tiles == 0 || n_blocks == 0) return hipSuccess;
   PrefillArgs a = a_in;
   a.n_ordered = 0;
+  // one block whose K and V of a KV head are at most 2 MB: the workgroups pull them into L2 up front
+  a.warm_kv = (n_blocks == 1 && a.keep_chunks == nullptr && (int64_t)a.total * a.D * 4 <= (2 << 20)) ? 1 : 0;
   const int G = a.Hq / a.Hkv;
   const int per_tile = a.Hkv * (G / a.heads_per_wg);  // workgroups per query tile (or pair)
   // causal: query tiles are paired; a local block pairs inside each segment, which
