@@ -115,6 +115,9 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
     // small causal launch: one query tile per workgroup, in the order the host laid out
     if (p >= a.n_ordered) return;
     tile_a = a.tile_order[p];
+    // the light half waits about a microsecond: its loads then queue behind those of the heavy
+    // half, whose workgroups set the length of the launch (the light ones have time to spare)
+    if (p >= (a.n_ordered + 1) / 2) __builtin_amdgcn_s_sleep(32);
   } else if (!causal) {
     if (p >= T) return;
     tile_a = T - 1 - p;
