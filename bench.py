@@ -41,7 +41,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # scaled by the same counters' reading for the plain-copy kernel aggregate_kv_kernel
 # (profiles/hbm_traffic_pmc_cfg2_prefill_cfg4_decode.txt).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_llama8b_prefill": (24708 + 16384) * 1024.0,   # prefill_mfma_kernel, per block launch (24 local, 8 sync)
+    "cfg2_llama8b_prefill": (24717 + 16384) * 1024.0,   # prefill_mfma_kernel, per block launch (24 local, 8 sync)
     # decode_stream_kernel (+ decode_combine_kernel in sync blocks), 24 local and 8 sync block-steps per step,
     # mean of the first and the last decoding step
     "cfg4_decode": (0.75 * (74295 + 2204) + 0.25 * (73720 + 8320 + 8781 + 128)) * 1024.0,
