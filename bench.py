@@ -431,7 +431,7 @@ def main() -> int:
         log("all %d blocks in one launch (upper bound, no block dependencies): %.3f ms, %.1f TFLOP/s"
             % (pb.M, batched * 1e3, roof["blocks_batched_tflops"]))
 
-    # the paper's analytic cost figures for this plan (Section VI-A, evaluation metrics)
+    # the paper's analytic cost figures for this plan (Section VII-A, evaluation metrics)
     cost = cost_report(pb.w.seg_lens, pb.sync, pb.w.n_q_heads, pb.w.n_kv_heads, pb.w.head_dim,
                        keep_fraction=pb.w.keep_fraction if pb.w.chunk_tokens else 1.0)
 

@@ -17,9 +17,10 @@
  *    k,v [tokens, Hkv, D].  Element type is params->dtype.  Device tensor
  *    pointers must be 16-byte aligned.
  *  - The caller owns every buffer.  The library allocates no device memory and
- *    keeps no state between calls.  Kernels are enqueued on `stream`
- *    (a hipStream_t cast to void*, NULL = default stream) and the call returns
- *    without waiting for them.
+ *    keeps nothing between calls that a result depends on (it remembers, per
+ *    device, the compute-unit count and which kernel attributes it has set).
+ *    Kernels are enqueued on `stream` (a hipStream_t cast to void*, NULL =
+ *    default stream) and the call returns without waiting for them.
  *  - Every failure is a return code; fedattn_last_error() gives the reason as
  *    text (thread-local).  Nothing is enqueued when a call fails validation.
  *  - Query head h reads KV head h / (Hq/Hkv) (grouped-query attention).
@@ -203,7 +204,7 @@ FEDATTN_API fedattn_status fedattn_aggregate_kv(const fedattn_params* params, co
 /*
  * Element-wise pieces of the decoder block around the attention operator, for the end-to-end
  * configuration (a block is attention and a feed-forward network, each with a residual
- * connection and a normalisation: Section III-B; the local forward of Section IV-A):
+ * connection and a normalisation: Section III-B; the local forward of Section IV-B):
  *   x += W_O Attention(RoPE(RMSNorm(x) W_QKV));  x += W_down (silu(gate) * up),
  *   [gate up] = RMSNorm(x) W_gate_up.
  * The matrix products are plain GEMMs and stay with the caller; these four passes are the

@@ -3,7 +3,7 @@ configuration: x += W_O Attn(RoPE(RMSNorm(x) W_QKV)); x += W_down(silu(gate) * u
 
 TEST INFRASTRUCTURE; never used by the GPU library.
 
-The paper's block (Section III-B, Section IV-A Phase I/II) is attention followed by
+The paper's block (Section III-B, Section IV-B Phase I/II) is attention followed by
 a feed-forward network with residual connections and normalisation; the end-to-end
 configuration fixes the Llama-style pieces around it: RMSNorm with unit gain,
 rotary position embedding on q and k with the token's index in the GLOBAL sequence,

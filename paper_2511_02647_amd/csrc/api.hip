@@ -7,6 +7,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "common.h"
 
 using namespace fedattn;
@@ -60,27 +62,24 @@ bool use_mfma_prefill(const fedattn_params* p) {
 // keep chunks that are not whole 64-row tiles: the MFMA path packs the kept rows first
 bool needs_row_packing(int chunk_tokens) { return chunk_tokens > 0 && chunk_tokens % kKvTile != 0; }
 
-int env_int(const char* name, int dflt) {
-  const char* s = getenv(name);
-  if (!s || !*s) return dflt;
-  const int v = atoi(s);
-  return v > 0 ? v : dflt;
-}
-
 // Decode splits every participant's cache segment into chunks of `rows` cache rows (a
 // multiple of the 64-row tile), one workgroup per (chunk, KV head).  The split aims at
-// one workgroup per CU: about n_cus / Hkv chunks over all segments.
+// one workgroup per CU of the current device: about n_cus / Hkv chunks over all segments.
+// The CU count is looked up once per device.
 int device_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cus = n;
-    else
-      cus = 256;
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> cus[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  const bool cached = dev >= 0 && dev < kMaxDevices;
+  if (cached) {
+    const int c = cus[dev].load(std::memory_order_relaxed);
+    if (c > 0) return c;
   }
-  return cus;
+  int n = 0;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+  if (cached) cus[dev].store(n, std::memory_order_relaxed);
+  return n;
 }
 
 int decode_target_chunks(int Hkv) {
@@ -89,8 +88,6 @@ int decode_target_chunks(int Hkv) {
 }
 
 int decode_chunk_rows(int64_t total_rows, int Hkv) {
-  static const int forced = env_int("FEDATTN_DECODE_CHUNK", 0);
-  if (forced > 0) return (forced + kKvTile - 1) / kKvTile * kKvTile;
   const int64_t target = decode_target_chunks(Hkv);
   int64_t rows = (total_rows + target - 1) / target;
   rows = (rows + kKvTile - 1) / kKvTile * kKvTile;
@@ -132,9 +129,9 @@ size_t decode_ws_bytes(const fedattn_params* p, int32_t capacity) {
   if (!(p->dtype == FEDATTN_BF16 && (p->head_dim == 64 || p->head_dim == 128))) return 16;
   const size_t G = (size_t)(p->n_q_heads / p->n_kv_heads);
   const size_t N = (size_t)p->n_participants;
-  // chunks <= sum_n (rows_n / chunk_rows + 1) <= target + N (or capacity/forced + N)
-  static const int forced = env_int("FEDATTN_DECODE_CHUNK", 0);
-  const size_t chunks = (forced > 0 ? (size_t)capacity / (size_t)forced + 1 : (size_t)decode_target_chunks(p->n_kv_heads)) + N;
+  // chunks <= sum_n (rows_n / chunk_rows + 1) <= target + N
+  (void)capacity;
+  const size_t chunks = (size_t)decode_target_chunks(p->n_kv_heads) + N;
   const size_t rows = (size_t)p->n_kv_heads * chunks * G * N;  // sync blocks: N*G query columns per chunk
   return align_up(rows * (size_t)p->head_dim * 4, 256) + align_up(rows * 8, 256) + decode_counter_bytes(p);
 }
@@ -329,9 +326,6 @@ static fedattn_status run_decode(bool fused, const fedattn_params* params, int32
     // local blocks count their chunks in at the end of their slice; the counters start at
     // zero and every launch leaves them at zero for the next one
     counters = reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(workspace) + need - decode_counter_bytes(params));
-    hipError_t e = launch_decode_zero_counters(counters, params->n_kv_heads * N, slices, (int64_t)slice_bytes,
-                                               reinterpret_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (counters): %s", hipGetErrorString(e));
   }
   fused = fused && mfma;
   const auto block_is_sync = [&](int b) {
@@ -388,6 +382,16 @@ static fedattn_status run_decode(bool fused, const fedattn_params* params, int32
     }
     return FEDATTN_OK;
   };
+  // everything that can fail validation is decided before the first launch
+  for (int b = 0; b < n_blocks && !(built[0] && built[1]); ++b) {
+    st = prepare(block_is_sync(b));
+    if (st != FEDATTN_OK) return st;
+  }
+  if (mfma) {
+    hipError_t e = launch_decode_zero_counters(counters, params->n_kv_heads * N, slices, (int64_t)slice_bytes,
+                                               reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "decode (counters): %s", hipGetErrorString(e));
+  }
   if (fused) {
     for (int kind = 0; kind < 2; ++kind) {
       int first = 0;

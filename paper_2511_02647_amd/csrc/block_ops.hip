@@ -2,7 +2,7 @@
 // end-to-end configuration: RMSNorm, rotary position embedding (with the split of the
 // fused QKV projection into the attention's q, k, v tensors), SwiGLU and the residual
 // add.  The block structure is the paper's (Section III-B: attention and a feed-forward
-// network, each with a residual connection and a normalisation; Section IV-A local
+// network, each with a residual connection and a normalisation; Section IV-B local
 // forward); the Llama-style variants are those of the configuration.  All four are
 // bandwidth-bound passes: 16-byte accesses with the nontemporal hint (every element is touched
 // once; without the hint RMSNorm ran at 4.9 TB/s instead of 6.5), fp32 arithmetic, bf16 at the

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "fedattn.h"
 
 namespace fedattn {
@@ -111,6 +113,19 @@ hipError_t launch_rope_split(const void* qkv, const int32_t* pos, void* q, void*
                              int Hkv, int D, float theta, hipStream_t s);
 hipError_t launch_swiglu(const void* gate_up, void* out, int64_t rows, int F, hipStream_t s);
 hipError_t launch_residual_add(float* x, const void* y, int64_t n, hipStream_t s);
+
+// A kernel's dynamic-LDS limit is a per-device attribute: set it the first time the kernel is
+// launched on a device (`done` holds one bit per device; setting it twice is harmless).
+inline hipError_t set_max_dynamic_lds_once(std::atomic<uint64_t>& done, const void* kernel, int bytes) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // Algorithm 1: block m = Ht + h (1-based) is the global-attention block iff h = H.
 __host__ __device__ inline bool sync_block_rule(int32_t H, int32_t block_idx) {

@@ -639,13 +639,10 @@ __global__ __launch_bounds__(64) void decode_rows_kernel(DecodeArgs a) {
 
 template <int D, bool COLSPLIT>
 hipError_t launch_stream_mode(const DecodeArgs& a, int n_z, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_stream_kernel<D, COLSPLIT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes<D>());
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_done{0};
+  hipError_t e0 = set_max_dynamic_lds_once(attr_done, reinterpret_cast<const void*>(&decode_stream_kernel<D, COLSPLIT>),
+                                           decode_smem_bytes<D>());
+  if (e0 != hipSuccess) return e0;
   const int qcols = COLSPLIT ? 64 : 16;
   dim3 grid((unsigned)(a.n_chunks * a.Hkv), (unsigned)((a.cols + qcols - 1) / qcols), (unsigned)n_z);
   hipLaunchKernelGGL((decode_stream_kernel<D, COLSPLIT>), grid, dim3(COLSPLIT ? 512 : 256), decode_smem_bytes<D>(), s, a);

@@ -552,13 +552,9 @@ hipError_t launch_pack_kept_rows(const PrefillArgs& a, int32_t* kept_rows, int32
 template <int D, int NG>
 hipError_t launch_prefill_mfma_t(const PrefillArgs& a, dim3 grid, hipStream_t s) {
   constexpr int smem = NG * 4 * KvTile<D, 1>::TILEB;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<D, NG>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_done{0};
+  hipError_t e0 = set_max_dynamic_lds_once(attr_done, reinterpret_cast<const void*>(&prefill_mfma_kernel<D, NG>), smem);
+  if (e0 != hipSuccess) return e0;
   hipLaunchKernelGGL((prefill_mfma_kernel<D, NG>), grid, dim3(256 * NG), smem, s, a);
   return hipGetLastError();
 }

@@ -3,7 +3,7 @@
 No arithmetic of the attention path lives here; these helpers only produce the
 `sync_override` flags that fedattn_prefill / fedattn_decode take, and the
 analytic per-participant cost figures the paper's evaluation reports beside the
-measured ones (Section VI-A, evaluation metrics: bits transmitted per
+measured ones (Section VII-A, evaluation metrics: bits transmitted per
 participant for the KV exchange; FLOPs and peak memory per participant).
 """
 from __future__ import annotations
@@ -27,7 +27,7 @@ def _spread(lo: int, hi: int, count: int) -> List[int]:
 
 
 def sync_schedule(name: str, n_blocks: int, n_syncs: int) -> List[bool]:
-    """The alternative placements of the global-attention blocks compared in Section VI-B
+    """The alternative placements of the global-attention blocks compared in Section VII-B
     (where to synchronise), for a budget of `n_syncs` global blocks among `n_blocks`.
 
     The paper names the schemes without printing block positions; the readings here:
@@ -100,7 +100,7 @@ def cost_report(seg_lens: Sequence[int], sync_flags: Sequence[bool], n_q_heads: 
     """Per-participant communication, attention FLOPs and KV memory of FedAttn.
 
     Communication: in every global block a participant sends its (kept) K and V rows once and
-    receives every other participant's kept rows (Section IV-A, Phase II; sparse exchange keeps
+    receives every other participant's kept rows (Section IV-B, Phase II; sparse exchange keeps
     the fraction `keep_fraction` of the remote rows).
     FLOPs: 4 D per visible (query, key) pair and query head (Q K^T and P V), pairs counted as
     the attention mask allows them: own segment in local blocks, the global sequence in global
