@@ -189,6 +189,24 @@ FEDATTN_API fedattn_status fedattn_decode_blocks_fused(const fedattn_params* par
                                            void* stream);
 
 /*
+ * fedattn_decode for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without the workspace) and bit-identical results; the split-KV partials and chunk
+ * counters live in an array of FEDATTN_STATIC_SCRATCH_BYTES that is part of the library's
+ * device code (every GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing.  Problems whose fedattn_workspace_bytes(DECODE) exceeds
+ * the array are rejected with FEDATTN_EWORKSPACE.  All calls on one GPU share that GPU's array:
+ * calls that may overlap (different streams, different threads) race and must be ordered by the
+ * caller; what a previous call left in the array does not matter.  The array's address is
+ * looked up at the first call on each device: make that call outside a graph capture.
+ */
+#define FEDATTN_STATIC_SCRATCH_BYTES (16u << 20)
+FEDATTN_API fedattn_status fedattn_decode_static(const fedattn_params* params, int32_t block_idx, const void* q,
+                                     const void* k_cache, const void* v_cache, void* out,
+                                     const int32_t* seg_offsets, const int32_t* seg_lens,
+                                     const int32_t* remote_lens, int32_t sync_override, void* stream);
+
+/*
  * KV aggregation of a sync block (Phase II): [K V] = sum_n Pi_n [k_n v_n], i.e.
  * row r of participant n's local k_n, v_n lands at global row seg_offsets[n] + r.
  *   k_local,v_local host arrays of N device pointers, entry n -> [len_n,Hkv,D]

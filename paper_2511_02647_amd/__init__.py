@@ -25,7 +25,7 @@ FEDATTN_MAX_PARTICIPANTS = 128
 
 EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill",
            "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_decode_blocks_fused",
-           "fedattn_aggregate_kv",
+           "fedattn_decode_static", "fedattn_aggregate_kv",
            "fedattn_rmsnorm", "fedattn_rope_split_qkv", "fedattn_swiglu", "fedattn_residual_add",
            "fedattn_last_error", "fedattn_version")
 
@@ -67,6 +67,8 @@ def load():
     lib.fedattn_prefill_blocks.restype = ctypes.c_int
     lib.fedattn_decode.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.fedattn_decode.restype = ctypes.c_int
+    lib.fedattn_decode_static.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.fedattn_decode_static.restype = ctypes.c_int
     lib.fedattn_decode_blocks.argtypes = [pp, i32, i32, vp, vp, vp, vp, i64, i64, vp, vp, vp, i32, vp, sz, vp]
     lib.fedattn_decode_blocks.restype = ctypes.c_int
     lib.fedattn_decode_blocks_fused.argtypes = lib.fedattn_decode_blocks.argtypes
@@ -184,6 +186,29 @@ def fedattn_decode(params: fedattn_params, block_idx: int, q: torch.Tensor, k_ca
                                  seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
                                  None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
                                  int(sync_override), _dev(workspace, "workspace"), ws_bytes, _stream(stream)))
+
+
+FEDATTN_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def fedattn_decode_static(params: fedattn_params, block_idx: int, q: torch.Tensor, k_cache: torch.Tensor,
+                          v_cache: torch.Tensor, out: torch.Tensor, seg_offsets, seg_lens, remote_lens=None,
+                          sync_override: int = -1, stream=None) -> None:
+    """fedattn_decode without a workspace (the library's built-in scratch array; allocates nothing)."""
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    lens = _host_i32(seg_lens, "seg_lens")
+    if seg.shape[0] != params.n_participants + 1 or lens.shape[0] != params.n_participants:
+        raise ValueError("seg_offsets / seg_lens have the wrong length")
+    rl = None
+    if remote_lens is not None:
+        rl = _host_i32(remote_lens, "remote_lens")
+        if rl.shape[0] != params.n_participants:
+            raise ValueError("remote_lens has the wrong length")
+    _check(load().fedattn_decode_static(ctypes.byref(params), int(block_idx), _dev(q, "q"), _dev(k_cache, "k_cache"),
+                                        _dev(v_cache, "v_cache"), _dev(out, "out"),
+                                        seg.ctypes.data_as(ctypes.c_void_p), lens.ctypes.data_as(ctypes.c_void_p),
+                                        None if rl is None else rl.ctypes.data_as(ctypes.c_void_p),
+                                        int(sync_override), _stream(stream)))
 
 
 def fedattn_decode_blocks(params: fedattn_params, block_idx0: int, n_blocks: int, q: torch.Tensor,

@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "common.h"
 
@@ -457,6 +458,58 @@ fedattn_status fedattn_decode(const fedattn_params* params, int32_t block_idx, c
                               size_t workspace_bytes, void* stream) {
   return fedattn_decode_blocks(params, block_idx, 1, q, k_cache, v_cache, out, 0, 0, seg_offsets, seg_lens,
                                remote_lens, sync_override, workspace, workspace_bytes, stream);
+}
+
+// ---- decode for callers that cannot allocate ---------------------------------------------
+// The split-KV partials and chunk counters of fedattn_decode live in this array instead of a
+// caller's workspace.  Every device the library runs on holds its own copy at its own address;
+// in host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[FEDATTN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxScratchDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxScratchDevices];  // device address of `scratch`, per device; NULL until looked up
+
+// Device address of the current device's copy of `scratch` (looked up once per device).
+fedattn_status static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxScratchDevices)
+    return fail(FEDATTN_EUNSUPPORTED, "device %d outside 0..%d", dev, kMaxScratchDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(FEDATTN_ELAUNCH, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return FEDATTN_OK;
+}
+}  // namespace
+
+fedattn_status fedattn_decode_static(const fedattn_params* params, int32_t block_idx, const void* q,
+                                     const void* k_cache, const void* v_cache, void* out,
+                                     const int32_t* seg_offsets, const int32_t* seg_lens,
+                                     const int32_t* remote_lens, int32_t sync_override, void* stream) {
+  fedattn_status st = check_params(params);
+  if (st != FEDATTN_OK) return st;
+  st = check_offsets(params, seg_offsets);
+  if (st != FEDATTN_OK) return st;
+  const size_t need = decode_ws_bytes(params, seg_offsets[params->n_participants]);
+  if (need > (size_t)FEDATTN_STATIC_SCRATCH_BYTES)
+    return fail(FEDATTN_EWORKSPACE,
+                "fedattn_decode_static: this problem needs %zu bytes of scratch, the built-in array holds %zu; "
+                "use fedattn_decode with a workspace",
+                need, (size_t)FEDATTN_STATIC_SCRATCH_BYTES);
+  void* ptr = nullptr;
+  st = static_scratch(&ptr);
+  if (st != FEDATTN_OK) return st;
+  return run_decode(false, params, block_idx, 1, q, k_cache, v_cache, out, 0, 0, seg_offsets, seg_lens, remote_lens,
+                    sync_override, ptr, (size_t)FEDATTN_STATIC_SCRATCH_BYTES, stream);
 }
 
 fedattn_status fedattn_aggregate_kv(const fedattn_params* params, const void* const* k_local,
