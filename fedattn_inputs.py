@@ -191,26 +191,30 @@ def keep_chunks(w: Workload, sync_round: int, seed: int = DEFAULT_SEED,
 
 
 def sample_rows(seg_offsets: np.ndarray, n_heads: int, n_random: int, seed: int,
-                salt: int = 0, tile: int = 64) -> Tuple[np.ndarray, np.ndarray]:
-    """(rows, heads) to check at sizes where the oracle cannot do every row:
-    per segment its first and last rows, the rows on both sides of every
-    `tile`-aligned position counted from the segment start and from token 0 that
-    fall near the segment's ends, plus n_random uniform (row, head) pairs."""
+                salt: int = 0, tile: int = 64, max_boundary_rows: int = 20000) -> Tuple[np.ndarray, np.ndarray]:
+    """(rows, heads) to check at sizes where the oracle cannot do every row: per segment its
+    first two and last two rows and the rows on both sides of EVERY `tile`-aligned position
+    inside it, counted from the segment start and from token 0 (the two grids on which the
+    kernels cut query and key tiles), plus n_random uniform (row, head) pairs.  If the boundary
+    rows number more than max_boundary_rows, every k-th of them is kept (segment ends always)."""
     g = stream(seed, 99, salt, _T_ROWS)
     total = int(seg_offsets[-1])
-    rows: List[int] = []
+    ends: List[int] = []
+    bounds: List[int] = []
     for n in range(len(seg_offsets) - 1):
         s, e = int(seg_offsets[n]), int(seg_offsets[n + 1])
         if e <= s:
             continue
-        cand = [s, s + 1, e - 2, e - 1]
+        ends.extend(r for r in (s, s + 1, e - 2, e - 1) if s <= r < e)
         for base in (s, 0):
-            for t in (tile, 2 * tile, 4 * tile):
-                for d in (-1, 0):
-                    cand.append(base + ((s - base) // tile) * tile + t + d)
-                    cand.append(base + ((e - 1 - base) // tile) * tile - t + tile + d)
-        rows.extend(r for r in cand if s <= r < e)
-    rows_a = np.array(sorted(set(rows)), dtype=np.int32)
+            first = base + ((s - base) // tile + 1) * tile      # first aligned position > s
+            for t in range(first, e, tile):
+                bounds.extend((t - 1, t))
+    bounds_a = np.array(sorted(set(bounds)), dtype=np.int64)
+    if bounds_a.shape[0] > max_boundary_rows:
+        step = -(-bounds_a.shape[0] // max_boundary_rows)
+        bounds_a = bounds_a[int(g.integers(0, step))::step]
+    rows_a = np.array(sorted(set(ends) | set(bounds_a.tolist())), dtype=np.int32)
     heads_a = g.integers(0, n_heads, size=rows_a.shape[0]).astype(np.int32)
     if n_random > 0 and total > 0:
         rr = g.integers(0, total, size=n_random).astype(np.int32)

@@ -53,7 +53,7 @@ typedef enum {
 
 typedef enum { FEDATTN_BF16 = 0, FEDATTN_F32 = 1 } fedattn_dtype;
 
-typedef enum { FEDATTN_OP_PREFILL = 0, FEDATTN_OP_DECODE = 1 } fedattn_op;
+typedef enum { FEDATTN_OP_PREFILL = 0, FEDATTN_OP_DECODE = 1, FEDATTN_OP_PREFILL_SYNC_LOCAL_KV = 2 } fedattn_op;
 
 typedef struct fedattn_params {
   int32_t n_participants; /* N, 1..FEDATTN_MAX_PARTICIPANTS */
@@ -75,6 +75,9 @@ FEDATTN_API int fedattn_is_sync_block(int32_t sync_interval, int32_t block_idx);
  *   FEDATTN_OP_PREFILL: `tokens` = total tokens; needed only when a keep-list is
  *     passed (chunk_tokens > 0); 0 otherwise.
  *   FEDATTN_OP_DECODE:  `tokens` = total cache capacity; chunk_tokens ignored.
+ *   FEDATTN_OP_PREFILL_SYNC_LOCAL_KV: `tokens` = total tokens; room for one aggregated copy of K
+ *     and V (used only when the participants' matrices do not lie back to back) plus the
+ *     keep-list's share (chunk_tokens > 0).
  * Returns 0 on invalid params. */
 FEDATTN_API size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t tokens,
                                int32_t chunk_tokens);
@@ -114,6 +117,30 @@ FEDATTN_API fedattn_status fedattn_prefill(const fedattn_params* params, int32_t
                                const int32_t* seg_offsets, const uint8_t* keep_chunks,
                                int32_t chunk_tokens, int32_t sync_override, void* workspace,
                                size_t workspace_bytes, void* stream);
+
+/*
+ * A sync block straight from the participants' own matrices: Phase II of Algorithm 1,
+ * [K V] = sum_n Pi_n [k_n v_n] followed by o_n = Attention(q_n, K, V), in one call.  The sum
+ * places row r of participant n at global row seg_offsets[n] + r; when the N matrices already
+ * lie back to back in participant order in device memory (k_local[n] = base + seg_offsets[n]
+ * rows, likewise v_local), that IS the aggregated matrix and the attention reads it in place:
+ * no copy, no extra launch.  Otherwise the matrices are first aggregated into the workspace
+ * (fedattn_aggregate_kv) and the attention reads the copy.  Always a sync block (the caller
+ * decides which blocks are, e.g. with fedattn_is_sync_block); results equal
+ * fedattn_aggregate_kv + fedattn_prefill with sync_override = 1.
+ *   q,out          device [total,Hq,D].
+ *   k_local,v_local host arrays of N device pointers, entry n -> [len_n,Hkv,D], 16-byte aligned
+ *                   (entries of empty segments are ignored).
+ *   keep_chunks, chunk_tokens  as in fedattn_prefill (sparse KV exchange).
+ *   workspace      device, >= fedattn_workspace_bytes(PREFILL_SYNC_LOCAL_KV); when the matrices
+ *                  lie back to back only the keep-list's share is used (the copy's share may
+ *                  be left out, and the workspace may be NULL without a keep-list).
+ */
+FEDATTN_API fedattn_status fedattn_prefill_sync_local_kv(const fedattn_params* params, const void* q,
+                                             const void* const* k_local, const void* const* v_local, void* out,
+                                             const int32_t* seg_offsets, const uint8_t* keep_chunks,
+                                             int32_t chunk_tokens, void* workspace, size_t workspace_bytes,
+                                             void* stream);
 
 /*
  * The same for n_blocks consecutive blocks block_idx0 .. block_idx0+n_blocks-1 in

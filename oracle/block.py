@@ -21,7 +21,7 @@ from typing import Callable, Dict, Optional
 
 import numpy as np
 
-from .rowwise import attend_block
+from .rowwise import attend_block, attend_rows
 
 Array = np.ndarray
 
@@ -76,11 +76,58 @@ def block_forward(x: Array, w: Dict[str, Array], seg_offsets, *, n_q_heads: int,
     # interface explicit here rather than implicit inside it
     q, k, v = (np.asarray(t.astype(np.float32), dtype=np.float64) for t in (q, k, v))
     attn = rd(attend_block(q, k, v, seg_offsets, is_sync=is_sync, causal=causal, keep_tok=keep_tok))
-    x1 = x + rd(attn.reshape(T, Hq * D) @ W["o"])
+    proj = rd(attn.reshape(T, Hq * D) @ W["o"])
+    x1 = x + proj
     # feed-forward half
     h2 = rd(rmsnorm(x1, eps))
     gu = rd(h2 @ W["gate_up"])
     F = W["down"].shape[0]
     act = rd(swiglu(gu[:, :F], gu[:, F:]))
-    x2 = x1 + rd(act @ W["down"])
-    return {"out": x2, "attn": attn, "q": q, "k": k, "v": v, "x_mid": x1, "act": act}
+    down = rd(act @ W["down"])
+    x2 = x1 + down
+    return {"out": x2, "attn": attn, "q": q, "k": k, "v": v, "x_mid": x1, "act": act, "proj": proj, "down": down}
+
+
+def block_forward_rows(x: Array, w: Dict[str, Array], seg_offsets, rows, *, n_q_heads: int, n_kv_heads: int,
+                       head_dim: int, is_sync: bool, keep_tok: Optional[Array] = None,
+                       pos: Optional[Array] = None, causal: bool = True, eps: float = 1e-6,
+                       theta: float = 10000.0, round_fn: Optional[Callable[[Array], Array]] = None) -> Dict[str, Array]:
+    """The block output for the token rows `rows` only, for sizes at which the whole block is out
+    of a CPU's reach.  A row of the output needs the whole block only through the keys and values
+    its attention sees, so K and V are computed for every token (normalisation, K/V columns of
+    the projection, rotary embedding of K) and everything else - the query, the attention of all
+    heads, the output projection, the feed-forward half - for the requested rows alone.  Same
+    steps, same order and same rounding hook as block_forward; returns 'out' [R, d_model],
+    'attn' [R, Hq, D], 'proj' and 'down' [R, d_model] (the two residual updates)."""
+    rd = (lambda a: a) if round_fn is None else (lambda a: np.asarray(round_fn(np.asarray(a, dtype=np.float32)), dtype=np.float64))
+    x = np.asarray(x, dtype=np.float64)
+    rows = np.asarray(rows, dtype=np.int64)
+    T, R = x.shape[0], rows.shape[0]
+    Hq, Hkv, D = n_q_heads, n_kv_heads, head_dim
+    W = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
+    if pos is None:
+        pos = np.arange(T)
+    pos = np.asarray(pos)
+    # keys and values of every token
+    h = rd(rmsnorm(x, eps))
+    k = rd(h @ W["qkv"][:, Hq * D:(Hq + Hkv) * D]).reshape(T, Hkv, D)
+    v = rd(h @ W["qkv"][:, (Hq + Hkv) * D:]).reshape(T, Hkv, D)
+    k = rd(rope(k, pos, theta))
+    # queries of the requested rows, scattered into an otherwise empty [T, Hq, D] array (the
+    # attention routine addresses queries by token index)
+    qr = rd(h[rows] @ W["qkv"][:, :Hq * D]).reshape(R, Hq, D)
+    qr = rd(rope(qr, pos[rows], theta))
+    q = np.zeros((T, Hq, D), dtype=np.float32)
+    q[rows] = qr.astype(np.float32)
+    k32, v32 = k.astype(np.float32), v.astype(np.float32)
+    rr = np.repeat(rows, Hq).astype(np.int32)
+    hh = np.tile(np.arange(Hq, dtype=np.int32), R)
+    attn = rd(attend_rows(q, k32, v32, seg_offsets, rr, hh, is_sync=is_sync, causal=causal, keep_tok=keep_tok)).reshape(R, Hq, D)
+    proj = rd(attn.reshape(R, Hq * D) @ W["o"])
+    x1 = x[rows] + proj
+    h2 = rd(rmsnorm(x1, eps))
+    gu = rd(h2 @ W["gate_up"])
+    F = W["down"].shape[0]
+    act = rd(swiglu(gu[:, :F], gu[:, F:]))
+    down = rd(act @ W["down"])
+    return {"out": x1 + down, "attn": attn, "proj": proj, "down": down, "x_mid": x1}

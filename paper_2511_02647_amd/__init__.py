@@ -20,10 +20,10 @@ LIB_PATH = os.environ.get("FEDATTN_LIB") or os.path.join(_HERE, "libfedattn.so")
 
 FEDATTN_OK, FEDATTN_EINVAL, FEDATTN_EUNSUPPORTED, FEDATTN_EWORKSPACE, FEDATTN_ELAUNCH = range(5)
 FEDATTN_BF16, FEDATTN_F32 = 0, 1
-FEDATTN_OP_PREFILL, FEDATTN_OP_DECODE = 0, 1
+FEDATTN_OP_PREFILL, FEDATTN_OP_DECODE, FEDATTN_OP_PREFILL_SYNC_LOCAL_KV = 0, 1, 2
 FEDATTN_MAX_PARTICIPANTS = 128
 
-EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill",
+EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill", "fedattn_prefill_sync_local_kv",
            "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_decode_blocks_fused",
            "fedattn_decode_static", "fedattn_aggregate_kv",
            "fedattn_rmsnorm", "fedattn_rope_split_qkv", "fedattn_swiglu", "fedattn_residual_add",
@@ -63,6 +63,8 @@ def load():
     lib.fedattn_workspace_bytes.restype = sz
     lib.fedattn_prefill.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
     lib.fedattn_prefill.restype = ctypes.c_int
+    lib.fedattn_prefill_sync_local_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.fedattn_prefill_sync_local_kv.restype = ctypes.c_int
     lib.fedattn_prefill_blocks.argtypes = [pp, i32, i32, vp, vp, vp, vp, i64, i64, vp, vp]
     lib.fedattn_prefill_blocks.restype = ctypes.c_int
     lib.fedattn_decode.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
@@ -156,6 +158,35 @@ def fedattn_prefill(params: fedattn_params, block_idx: int, q: torch.Tensor, k: 
                                   _dev(workspace, "workspace"), ws_bytes, _stream(stream)))
 
 
+def _local_ptrs(local: Sequence[Optional[torch.Tensor]], n: int, name: str):
+    arr = (ctypes.c_void_p * n)()
+    for i in range(n):
+        t = local[i]
+        if t is None or t.numel() == 0:
+            arr[i] = None
+        else:
+            if not (t.is_cuda and t.is_contiguous()):
+                raise TypeError("%s[%d] must be a contiguous device tensor" % (name, i))
+            arr[i] = t.data_ptr()
+    return arr
+
+
+def fedattn_prefill_sync_local_kv(params: fedattn_params, q: torch.Tensor, k_local: Sequence[Optional[torch.Tensor]],
+                                  v_local: Sequence[Optional[torch.Tensor]], out: torch.Tensor, seg_offsets,
+                                  keep_chunks: Optional[torch.Tensor] = None, chunk_tokens: int = 0,
+                                  workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    seg = _host_i32(seg_offsets, "seg_offsets")
+    n = params.n_participants
+    if seg.shape[0] != n + 1 or len(k_local) != n or len(v_local) != n:
+        raise ValueError("k_local / v_local / seg_offsets have the wrong length")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().fedattn_prefill_sync_local_kv(ctypes.byref(params), _dev(q, "q"), _local_ptrs(k_local, n, "k_local"),
+                                                _local_ptrs(v_local, n, "v_local"), _dev(out, "out"),
+                                                seg.ctypes.data_as(ctypes.c_void_p), _dev(keep_chunks, "keep_chunks"),
+                                                int(chunk_tokens), _dev(workspace, "workspace"), ws_bytes,
+                                                _stream(stream)))
+
+
 def fedattn_prefill_blocks(params: fedattn_params, block_idx0: int, n_blocks: int, q: torch.Tensor,
                            k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, q_block_stride: int,
                            kv_block_stride: int, seg_offsets, stream=None) -> None:
@@ -247,16 +278,7 @@ def fedattn_aggregate_kv(params: fedattn_params, k_local: Sequence[Optional[torc
     n = params.n_participants
     if seg.shape[0] != n + 1 or len(k_local) != n or len(v_local) != n:
         raise ValueError("k_local / v_local / seg_offsets have the wrong length")
-    kp = (ctypes.c_void_p * n)()
-    vp = (ctypes.c_void_p * n)()
-    for i in range(n):
-        for arr, t, nm in ((kp, k_local[i], "k_local"), (vp, v_local[i], "v_local")):
-            if t is None or t.numel() == 0:
-                arr[i] = None
-            else:
-                if not (t.is_cuda and t.is_contiguous()):
-                    raise TypeError("%s[%d] must be a contiguous device tensor" % (nm, i))
-                arr[i] = t.data_ptr()
+    kp, vp = _local_ptrs(k_local, n, "k_local"), _local_ptrs(v_local, n, "v_local")
     _check(load().fedattn_aggregate_kv(ctypes.byref(params), kp, vp, seg.ctypes.data_as(ctypes.c_void_p),
                                        _dev(k_global, "k_global"), _dev(v_global, "v_global"), _stream(stream)))
 

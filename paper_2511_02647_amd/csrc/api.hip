@@ -137,6 +137,11 @@ size_t decode_ws_bytes(const fedattn_params* p, int32_t capacity) {
   return align_up(rows * (size_t)p->head_dim * 4, 256) + align_up(rows * 8, 256) + decode_counter_bytes(p);
 }
 
+// fedattn_prefill_sync_local_kv, participants' K/V not back to back: room for one aggregated copy each
+size_t local_kv_copy_bytes(const fedattn_params* p, int32_t tokens) {
+  return align_up((size_t)tokens * (size_t)p->n_kv_heads * (size_t)p->head_dim * (p->dtype == FEDATTN_BF16 ? 2 : 4), 256);
+}
+
 fedattn_status run_prefill(const fedattn_params* p, int32_t block_idx0, int32_t n_blocks, const void* q,
                            const void* k, const void* v, void* out, int64_t q_stride, int64_t kv_stride,
                            const int32_t* seg, const uint8_t* keep_chunks, int32_t chunk_tokens,
@@ -252,6 +257,8 @@ size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t op, int32_t
   if (check_params(params) != FEDATTN_OK || tokens < 0) return 0;
   if (op == FEDATTN_OP_PREFILL) return chunk_tokens > 0 ? prefill_ws_layout(params, tokens, chunk_tokens).total : 0;
   if (op == FEDATTN_OP_DECODE) return decode_ws_bytes(params, tokens);
+  if (op == FEDATTN_OP_PREFILL_SYNC_LOCAL_KV)
+    return 2 * local_kv_copy_bytes(params, tokens) + (chunk_tokens > 0 ? prefill_ws_layout(params, tokens, chunk_tokens).total : 0);
   fail(FEDATTN_EINVAL, "unknown op %d", op);
   return 0;
 }
@@ -262,6 +269,70 @@ fedattn_status fedattn_prefill(const fedattn_params* params, int32_t block_idx, 
                                size_t workspace_bytes, void* stream) {
   return run_prefill(params, block_idx, 1, q, k, v, out, 0, 0, seg_offsets, keep_chunks, chunk_tokens,
                      sync_override, workspace, workspace_bytes, stream);
+}
+
+fedattn_status fedattn_prefill_sync_local_kv(const fedattn_params* params, const void* q, const void* const* k_local,
+                                             const void* const* v_local, void* out, const int32_t* seg_offsets,
+                                             const uint8_t* keep_chunks, int32_t chunk_tokens, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  fedattn_status st = check_params(params);
+  if (st != FEDATTN_OK) return st;
+  st = check_offsets(params, seg_offsets);
+  if (st != FEDATTN_OK) return st;
+  if (!k_local || !v_local) return fail(FEDATTN_EINVAL, "k_local and v_local must not be NULL");
+  const int N = params->n_participants;
+  const int32_t total = seg_offsets[N];
+  if (total == 0) return FEDATTN_OK;
+  const int64_t row_bytes = (int64_t)params->n_kv_heads * params->head_dim * (params->dtype == FEDATTN_BF16 ? 2 : 4);
+  // Sum_n Pi_n [k_n v_n] puts row r of participant n at global row seg_offsets[n] + r.  If every
+  // participant's matrices already start that many rows behind one common base address, the
+  // aggregated matrices exist as they are and the attention reads them in place.
+  const unsigned char* k_base = nullptr;
+  const unsigned char* v_base = nullptr;
+  bool in_place = true;
+  for (int n = 0; n < N; ++n) {
+    if (seg_offsets[n + 1] == seg_offsets[n]) continue;
+    if (!k_local[n] || !v_local[n]) return fail(FEDATTN_EINVAL, "local K/V of participant %d is NULL", n);
+    if (!aligned16(k_local[n]) || !aligned16(v_local[n]))
+      return fail(FEDATTN_EINVAL, "local K/V of participant %d is not 16-byte aligned", n);
+    const unsigned char* kb = reinterpret_cast<const unsigned char*>(k_local[n]) - (int64_t)seg_offsets[n] * row_bytes;
+    const unsigned char* vb = reinterpret_cast<const unsigned char*>(v_local[n]) - (int64_t)seg_offsets[n] * row_bytes;
+    if (!k_base) {
+      k_base = kb;
+      v_base = vb;
+    } else if (kb != k_base || vb != v_base) {
+      in_place = false;
+    }
+  }
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  size_t ws_left = workspace ? workspace_bytes : 0;
+  if (!in_place) {
+    const size_t copy = local_kv_copy_bytes(params, total);
+    if (!workspace || workspace_bytes < 2 * copy)
+      return fail(FEDATTN_EWORKSPACE,
+                  "the participants' K/V do not lie back to back: aggregating them needs %zu workspace bytes, got %zu",
+                  2 * copy, workspace_bytes);
+    if (!aligned16(workspace)) return fail(FEDATTN_EINVAL, "workspace must be 16-byte aligned");
+    if (keep_chunks && chunk_tokens > 0 &&
+        workspace_bytes < 2 * copy + prefill_ws_layout(params, total, chunk_tokens).total)
+      return fail(FEDATTN_EWORKSPACE, "workspace too small for the aggregated copy and the keep-list (%zu bytes needed)",
+                  2 * copy + prefill_ws_layout(params, total, chunk_tokens).total);
+    k_base = ws;
+    v_base = ws + copy;
+    ws += 2 * copy;
+    ws_left -= 2 * copy;
+  }
+  // q, out and the keep-list arguments are validated by the prefill path; when they pass,
+  // nothing there can fail short of a launch error, so the copy is enqueued only for valid calls
+  if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(FEDATTN_EINVAL, "q and out must be non-NULL and 16-byte aligned");
+  if (keep_chunks && chunk_tokens <= 0) return fail(FEDATTN_EINVAL, "chunk_tokens must be positive with a keep-list");
+  if (!in_place) {
+    st = fedattn_aggregate_kv(params, k_local, v_local, seg_offsets, const_cast<unsigned char*>(k_base),
+                              const_cast<unsigned char*>(v_base), stream);
+    if (st != FEDATTN_OK) return st;
+  }
+  return run_prefill(params, 0, 1, q, k_base, v_base, out, 0, 0, seg_offsets, keep_chunks, chunk_tokens, 1,
+                     ws_left ? ws : nullptr, ws_left, stream);
 }
 
 fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,

@@ -137,3 +137,31 @@ def test_rounding_hook_touches_interfaces_only():
     ident = ob.block_forward(x, w, [0, 12], round_fn=lambda a: (calls.append(a.shape), a)[1], **kw)
     assert len(calls) == 10         # h, qkv, q, k, attn, o-proj, h2, gate_up, act, down
     assert np.allclose(ident["out"], exact["out"], atol=1e-5)      # float32 pass-through of the hook only
+
+
+@pytest.mark.parametrize("is_sync", [False, True])
+def test_row_sampled_block_matches_the_library_block_on_those_rows(is_sync):
+    """block_forward_rows (keys and values for every token, everything else for the requested rows
+    only) against the block assembled from library routines, and against block_forward, with a
+    keep-list and with the rounding hook."""
+    d_model, Hq, Hkv, D, F = 48, 4, 2, 16, 40
+    seg = np.array([0, 9, 9, 20, 31])
+    T = 31
+    x = RNG.standard_normal((T, d_model))
+    w = _weights(d_model, Hq, Hkv, D, F)
+    rows = np.array([0, 8, 9, 19, 20, 30, 14])
+    kw = dict(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, is_sync=is_sync)
+    got = ob.block_forward_rows(x, w, seg, rows, **kw)
+    i, j = np.arange(T)[:, None], np.arange(T)[None, :]
+    mask = j <= i
+    owner = np.searchsorted(seg, np.arange(T), side="right")
+    if not is_sync:
+        mask = mask & (owner[:, None] == owner[None, :])
+    assert np.allclose(got["out"], _torch_block(x, w, Hq, Hkv, D, mask)[rows], rtol=1e-10, atol=1e-10)
+    # sparse exchange and the rounding hook: the same numbers as the full block on those rows
+    keep = (RNG.random(T) < 0.5).astype(np.uint8)
+    rnd = lambda a: np.round(a * 64.0) / 64.0
+    full = ob.block_forward(x, w, seg, keep_tok=keep, round_fn=rnd, **kw)
+    part = ob.block_forward_rows(x, w, seg, rows, keep_tok=keep, round_fn=rnd, **kw)
+    assert np.allclose(part["out"], full["out"][rows], rtol=1e-12, atol=1e-12)
+    assert np.allclose(part["attn"], full["attn"][rows], rtol=1e-12, atol=1e-12)

@@ -273,16 +273,18 @@ def test_cfg2_full_size():
                       block=b, dtype=BF16)
         sync = oracle.is_sync_block(w.sync_interval, b)
         assert sync == (b == 3)
-        _sampled_check(q, k, v, seg, got, is_sync=sync, n_random=3000, what="cfg2 block %d" % b, salt=b)
+        _sampled_check(q, k, v, seg, got, is_sync=sync, n_random=4096, what="cfg2 block %d" % b, salt=b)
 
 
 def test_cfg3_full_size_sync_interval_sweep():
+    """Every H of the sweep gets its own sample: all tile-boundary rows plus 4096 random (row, head)
+    pairs per (block, H); launches of the same kind of block must also agree bit for bit."""
     w = fi.workload("cfg3_hetero_prefill")
     seg = w.seg_offsets
-    results = {}
     for b in (0, 31):
         q, k, v = fi.prefill_block(w, b)
         tq, tk, tv = dev(q, BF16), dev(k, BF16), dev(v, BF16)
+        results = {}
         for H in (1, 4, 8, 32):
             sync = oracle.is_sync_block(H, b)
             say("cfg3 block %d H=%d (%s)" % (b, H, "sync" if sync else "local"))
@@ -292,12 +294,10 @@ def test_cfg3_full_size_sync_interval_sweep():
             torch.cuda.synchronize()
             if (b, sync) in results:     # same block, same kind of block: identical output
                 assert torch.equal(results[(b, sync)], out)
-                continue
             results[(b, sync)] = out
-            _sampled_check(q, k, v, seg, host(out), is_sync=sync, n_random=2048,
-                           what="cfg3 block %d %s" % (b, "sync" if sync else "local"), salt=10 + b)
-        results.clear()
-        del tq, tk, tv
+            _sampled_check(q, k, v, seg, host(out), is_sync=sync, n_random=4096,
+                           what="cfg3 block %d H=%d %s" % (b, H, "sync" if sync else "local"), salt=10 + 100 * H + b)
+        del tq, tk, tv, results
 
 
 def test_cfg5_sparse_sync_full_size():
@@ -311,7 +311,7 @@ def test_cfg5_sparse_sync_full_size():
         say("cfg5 block %d (%s)" % (b, "sparse sync" if sync else "local"))
         got = prefill(q, k, v, seg, Hq=w.n_q_heads, Hkv=w.n_kv_heads, D=w.head_dim, H=w.sync_interval,
                       block=b, dtype=BF16, keep_chunks=flags, chunk_tokens=w.chunk_tokens)
-        _sampled_check(q, k, v, seg, got, is_sync=sync, n_random=1024, keep_tok=kt,
+        _sampled_check(q, k, v, seg, got, is_sync=sync, n_random=4096, keep_tok=kt,
                        what="cfg5 block %d" % b, salt=20 + b)
 
 
@@ -503,22 +503,33 @@ def test_decode_small(N, Hq, Hkv, D, dtype):
 
 
 def test_cfg4_decode_full_size():
+    """All 16 x 32 output rows at decoding steps {0, 1, 127, 255} of blocks {0, 3, 16, 31} (local: 0, 16;
+    sync: 3, 31) plus eight seeded random (step, block) pairs; sync blocks under both readings of
+    what the other participants' caches show (everything cached / the prompt only)."""
     w = fi.workload("cfg4_decode")
     seg = w.seg_offsets
     prompt = np.full(w.n_participants, 1024, dtype=np.int32)
-    for b in (0, 3):
+    cases = [(b, s) for b in (0, 3, 16, 31) for s in (0, 1, 127, 255)]
+    g = fi.stream(fi.DEFAULT_SEED, 98, 0, 5)
+    cases += [(int(b), int(s)) for b, s in zip(g.integers(0, w.n_blocks, size=8), g.integers(0, w.decode_steps, size=8))]
+    p = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, w.sync_interval, BF16)
+    ws = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, int(seg[-1])), dtype=torch.uint8, device="cuda")
+    for b in sorted(set(c[0] for c in cases)):
         kc, vc = fi.decode_cache_block(w, b)
-        for step in (0, 255):
+        tk, tv = dev(kc, BF16), dev(vc, BF16)
+        sync = oracle.is_sync_block(w.sync_interval, b)
+        for step in sorted(set(c[1] for c in cases if c[0] == b)):
             lens = prompt + step + 1
             q = fi.decode_query(w, step, b)
-            sync = oracle.is_sync_block(w.sync_interval, b)
-            readings = [None, prompt] if sync else [None]
-            for rl in readings:
+            tq = dev(q, BF16)
+            for rl in ([None, prompt] if sync else [None]):
                 say("cfg4 block %d step %d remote=%s" % (b, step, rl is not None))
-                got = decode(q, kc, vc, seg, lens, Hq=w.n_q_heads, Hkv=w.n_kv_heads, D=w.head_dim,
-                             H=w.sync_interval, block=b, dtype=BF16, remote_lens=rl)
+                out = torch.full_like(tq, float("nan"))
+                fa.fedattn_decode(p, b, tq, tk, tv, out, seg, lens, remote_lens=rl, workspace=ws)
+                torch.cuda.synchronize()
                 ref = oracle.decode_step(q, kc, vc, seg, lens, is_sync=sync, remote_lens=rl)
-                check(got, ref, BF16, "cfg4 block %d step %d %s" % (b, step, "prompt-only remote" if rl is not None else "all cached"))
+                check(host(out), ref, BF16, "cfg4 block %d step %d %s" % (b, step, "prompt-only remote" if rl is not None else "all cached"))
+        del tk, tv
 
 
 def test_decode_local_chunk_merge_in_kernel_with_dirty_workspace():
@@ -655,6 +666,44 @@ def test_hip_graph_replays_match_eager():
         torch.cuda.synchronize()
         for got, want, name in zip((out, out_sparse, od), ref, ("prefill", "sparse prefill", "decode")):
             assert torch.equal(got, want), "graph replay %d: %s differs from the eager run" % (rep, name)
+
+
+@pytest.mark.parametrize("dtype", [BF16, F32])
+def test_prefill_sync_local_kv_in_place_and_through_a_copy(dtype):
+    """Phase II in one call from the participants' own K/V: read in place when they lie back to back
+    in participant order, aggregated into the workspace first when they do not; both bit-equal to
+    fedattn_aggregate_kv + fedattn_prefill, dense and under sparse exchange."""
+    seg = np.array([0, 100, 100, 260, 420], dtype=np.int32)
+    N, Hq, Hkv, D = 4, 8, 2, 128 if dtype == BF16 else 64
+    q, k, v = rand_block(91, 420, Hq, Hkv, D, bf16=dtype == BF16)
+    p = fa.make_params(N, Hq, Hkv, D, 3, dtype)
+    tq, tk, tv = dev(q, dtype), dev(k, dtype), dev(v, dtype)
+    flags = (np.random.default_rng(92).random(int(fi.chunk_counts(np.diff(seg), 16).sum())) < 0.4).astype(np.uint8)
+    tflags = torch.from_numpy(flags).cuda()
+    kt = oracle.expand_keep_chunks(flags, seg, 16)
+    views_k = [tk[seg[n]:seg[n + 1]] for n in range(N)]
+    views_v = [tv[seg[n]:seg[n + 1]] for n in range(N)]
+    apart_k = [x.clone() if x.numel() else None for x in views_k]      # separate allocations
+    apart_v = [x.clone() if x.numel() else None for x in views_v]
+    ws_pre = torch.empty(max(16, fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_PREFILL, 420, 16)), dtype=torch.uint8, device="cuda")
+    ws_all = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_PREFILL_SYNC_LOCAL_KV, 420, 16), dtype=torch.uint8, device="cuda")
+    for sparse in (False, True):
+        kc, ct = (tflags, 16) if sparse else (None, 0)
+        want = torch.full_like(tq, float("nan"))
+        fa.fedattn_prefill(p, 0, tq, tk, tv, want, seg, keep_chunks=kc, chunk_tokens=ct, sync_override=1, workspace=ws_pre)
+        torch.cuda.synchronize()
+        ref = oracle.attend_block(q, k, v, seg, is_sync=True, keep_tok=kt if sparse else None)
+        check(host(want), ref, dtype, "sync block via fedattn_prefill, sparse=%d" % sparse)
+        for name, kl, vl, ws in [("in place", views_k, views_v, ws_pre if sparse else None), ("copied", apart_k, apart_v, ws_all)]:
+            say("prefill_sync_local_kv %s %s sparse=%d" % (dtype, name, sparse))
+            got = torch.full_like(tq, float("nan"))
+            fa.fedattn_prefill_sync_local_kv(p, tq, kl, vl, got, seg, keep_chunks=kc, chunk_tokens=ct, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(got, want), "Phase II from local K/V (%s, sparse=%d) differs" % (name, sparse)
+    with pytest.raises(fa.FedAttnError) as e:     # matrices apart and nowhere to aggregate them
+        fa.fedattn_prefill_sync_local_kv(p, tq, apart_k, apart_v, torch.empty_like(tq), seg)
+    assert e.value.status == fa.FEDATTN_EWORKSPACE
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("dtype", [BF16, F32])

@@ -307,6 +307,32 @@ def test_sparse_exchange_limits():
     np.testing.assert_allclose(got[16:40], sdpa(q[sel1], k[sel1], v[sel1])[16:40], atol=1e-12)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_sparse_exchange_matches_library_attention_with_an_explicit_mask(causal):
+    """Sparse KV exchange (own rows complete, a remote row visible only if its flag is set;
+    adaptive KV aggregation of Section V), causal and bidirectional, against library attention
+    under a visibility matrix written out here token by token, independently of the oracle."""
+    seg = [0, 11, 11, 30, 47]
+    L, Hq, Hkv, D = 47, 4, 2, 16
+    q, k, v = rand_qkv(16, L, Hq, Hkv, D)
+    g = np.random.default_rng(17)
+    keep = (g.random(L) < 0.4).astype(np.uint8)
+    keep[30:47] = 0                    # the last participant shares nothing, yet sees itself
+    owner = np.zeros(L, dtype=np.int64)
+    for n in range(len(seg) - 1):
+        owner[seg[n]:seg[n + 1]] = n
+    mask = np.zeros((L, L), dtype=bool)
+    for i in range(L):
+        for j in range(L):
+            if causal and j > i:
+                continue
+            mask[i, j] = owner[i] == owner[j] or keep[j] == 1
+    got = oracle.attend_block(q, k, v, seg, is_sync=True, causal=causal, keep_tok=keep)
+    np.testing.assert_allclose(got, sdpa(q, k, v, mask=mask), atol=1e-12)
+    # and the mask does bind: the dense sync block differs
+    assert np.abs(got - oracle.attend_block(q, k, v, seg, is_sync=True, causal=causal)).max() > 1e-3
+
+
 def test_chunk_expansion_ragged_tail():
     seg = [0, 10, 10, 27]
     flags = np.array([1, 0, 0, 1, 1], dtype=np.uint8)   # 2 chunks, 0 chunks, 3 chunks of 8
