@@ -1,19 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark of the FedAttn attention hot path on one MI355X.
 
-A step is one pass of the whole path over one batch of synthetic input: the
-attention of all M Transformer blocks of the workload, block after block (one
-launch per block, as the blocks of a model depend on each other), local blocks
-attending inside each participant's segment and every H-th block aggregating
-the participants' K/V (fedattn_aggregate_kv) and attending over the global KV.
-Inputs are resident in HBM before the timed region.
+A step is one pass of the whole path over one batch of synthetic input: the attention of
+all M Transformer blocks of a workload, block after block (one launch per block, as the
+blocks of a model depend on each other), local blocks attending inside each participant's
+segment (fedattn_prefill) and every H-th block running Phase II from the participants' own
+K/V (fedattn_prefill_sync_local_kv: aggregation + global attention; the participants'
+matrices lie back to back in HBM, so the aggregated matrix is read in place).  Inputs are
+resident in HBM before the timed region; a step's launches are replayed from a HIP graph
+(checked against the eager step first), so the timed region measures the GPU, not Python.
 
-Prints ONE JSON line.  `value` is useful attention TFLOP/s of the headline
-prefill workload (4*D*Hq*visible pairs; masked pairs and softmax not counted).
-`roofline` is for the dominant kernel (the MFMA prefill kernel), `decode`
-carries the split-KV decode kernel's achieved HBM GB/s on the decode workload,
-and `cpu_baseline` is the fp64 oracle timed on this machine's host cores on a
-bounded sample of the same workload.
+Legs (each with its own `roofline` object):
+  cfg3        heterogeneous prefill, N = 8 uneven segments, the H sweep {1, 4, 8, 32} of the
+              configuration in one step (4 x 32 launches); also reported per H.  HEADLINE:
+              the largest single-GPU workload.
+  cfg5        sparse-sync prefill, 16 x 4096 tokens, a quarter of the 64-token chunks exchanged.
+  cfg2        Llama-3-8B shape, 4 x 512 tokens (the smallest bf16 workload; launch-dominated).
+  decode      cfg4: 16 participants, 256 decoding steps x 32 blocks, every step replayed from
+              its own graph (the cache lengths grow step by step), GB/s over the whole run.
+
+Prints ONE JSON line.  `value` is useful attention TFLOP/s of the headline workload
+(4*D*Hq*visible pairs; masked pairs and softmax not counted).  `roofline` is for the
+dominant kernel of the headline (the MFMA prefill kernel); `decode.roofline` for the
+streaming decode kernels; `cpu_baseline` is the fp64 oracle timed on this machine's host
+cores on a bounded sample of the headline workload.
 """
 from __future__ import annotations
 
@@ -37,15 +47,21 @@ from paper_2511_02647_amd.planning import cost_report  # noqa: E402
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# scaled by the same counters' reading for the plain-copy kernel aggregate_kv_kernel
-# (profiles/hbm_traffic_pmc_cfg2_prefill_cfg4_decode.txt).
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2_llama8b_prefill": (24717 + 16384) * 1024.0,   # prefill_mfma_kernel, per block launch (24 local, 8 sync)
-    # decode_stream_kernel (+ decode_combine_kernel in sync blocks), 24 local and 8 sync block-steps per step,
-    # mean of the first and the last decoding step
-    "cfg4_decode": (0.75 * (74295 + 2204) + 0.25 * (73720 + 8320 + 8781 + 128)) * 1024.0,
+# Figures that only a profiler run can give (hardware counters), copied from the rocprofv3
+# summaries under profiles/ (each summary names the command that produced it; the CPU test
+# tests/test_bench_constants.py checks that the numbers here are the ones in those files).
+#   traffic_bytes  HBM bytes per launch, FETCH_SIZE + WRITE_SIZE scaled by the same counters'
+#                  reading for a plain copy kernel of known size (aggregate_kv_kernel)
+#   mfma_util      SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES): share of the cycles a
+#                  busy CU's matrix pipes were busy
+PMC = {
+    "cfg3_H4": {"source": None, "traffic_bytes": None, "mfma_util": None},
+    "cfg5": {"source": None, "traffic_bytes": None, "mfma_util": None},
+    "cfg2": {"source": None, "traffic_bytes": None, "mfma_util": None},
+    "decode": {"source": None, "traffic_bytes": None},
 }
+
+CFG3_SWEEP = (1, 4, 8, 32)
 
 
 def log(msg: str) -> None:
@@ -82,14 +98,75 @@ def keep_tokens(flags: np.ndarray, seg: np.ndarray, chunk_tokens: int) -> np.nda
     return out
 
 
+DEVICE_WARMUP_S = 0.3
+
+
+def device_warmup(fn, seconds: float = DEVICE_WARMUP_S) -> None:
+    """Untimed work before a measurement: the GPU raises its clock over the first tenths of a
+    second of sustained load, and a throughput figure should be the sustained one."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+
+
+def timed_replays(fns, steps: int, warmup: int):
+    """`fns`: the graph replays that make up one step, in order.  Runs `warmup` untimed steps,
+    then exactly `steps` timed ones between two synchronisations; every replay is also bracketed
+    by HIP events on the stream it is launched on.  Returns (wall seconds per step,
+    ms[steps][len(fns)] by events)."""
+    def one():
+        for f in fns:
+            f()
+    device_warmup(one)
+    for _ in range(warmup):
+        one()
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in fns]
+           for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for i, f in enumerate(fns):
+            evs[s][i][0].record()
+            f()
+            evs[s][i][1].record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    ms = np.array([[a.elapsed_time(b) for a, b in row] for row in evs])
+    return wall, ms
+
+
+def capture(fn, check_tensor: torch.Tensor):
+    """`fn`'s launches captured into a HIP graph; two replays are compared with the eager run."""
+    check_tensor.zero_()
+    fn()
+    torch.cuda.synchronize()
+    ref = check_tensor.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fn()
+    torch.cuda.synchronize()
+    for rep in range(2):
+        check_tensor.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        if not torch.equal(check_tensor, ref):
+            raise RuntimeError("graph replay %d differs from the eager run" % rep)
+    return graph
+
+
 class PrefillBench:
-    def __init__(self, name: str, n_data_blocks: int | None = None, H: int | None = None, aggregate: bool = True):
+    """Resident inputs of one prefill workload and the launches of a step at a given H."""
+
+    def __init__(self, name: str, n_data_blocks: int | None = None):
         self.w = fi.workload(name)
         w = self.w
-        self.H = w.sync_interval if H is None else H
         self.seg = w.seg_offsets
         self.M = w.n_blocks
-        self.aggregate = aggregate
         nd = self.M if n_data_blocks is None else min(n_data_blocks, self.M)
         self.nd = nd
         t0 = time.time()
@@ -100,100 +177,117 @@ class PrefillBench:
         self.v = torch.stack([to_dev_bf16(b[2]) for b in blocks])
         del blocks
         self.out = torch.empty_like(self.q)
-        self.kg = torch.empty_like(self.k[0])
-        self.vg = torch.empty_like(self.v[0])
-        self.p = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, self.H, torch.bfloat16)
         self.keep = None
         self.ws = None
         self.keep_tok = None
+        self.p = {}
         if w.chunk_tokens:
-            flags = [fi.keep_chunks(w, t) for t in range(max(1, self.M // max(self.H, 1)))]
+            rounds = max(1, self.M // max(w.sync_interval, 1))
+            flags = [fi.keep_chunks(w, t) for t in range(rounds)]
             self.keep = [torch.from_numpy(f).to("cuda") for f in flags]
             self.keep_tok = [keep_tokens(f, self.seg, w.chunk_tokens) for f in flags]
-            nbytes = fa.fedattn_workspace_bytes(self.p, fa.FEDATTN_OP_PREFILL, w.total_tokens, w.chunk_tokens)
+            nbytes = fa.fedattn_workspace_bytes(self.params(w.sync_interval), fa.FEDATTN_OP_PREFILL, w.total_tokens,
+                                                w.chunk_tokens)
             self.ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        self.sync = [fa.fedattn_is_sync_block(self.H, b) for b in range(self.M)]
-        fl = 4 * w.head_dim * w.n_q_heads
-        self.flops_block = []
-        for b in range(self.M):
-            kt = None
-            if self.sync[b] and self.keep_tok is not None:
-                kt = self.keep_tok[(b // self.H) % len(self.keep_tok)]
-            self.flops_block.append(fl * visible_pairs(self.seg, self.sync[b], kt))
-        self.flops_step = float(sum(self.flops_block))
         torch.cuda.synchronize()
-        log("%s: %d blocks (%d resident), H=%d, %d sync, %.1f GFLOP/step, inputs ready in %.1f s"
-            % (name, self.M, nd, self.H, sum(self.sync), self.flops_step / 1e9, time.time() - t0))
+        log("%s: %d blocks (%d distinct input blocks resident, %.2f GB), inputs ready in %.1f s"
+            % (name, self.M, nd, (2 * self.q.numel() + 2 * self.k.numel()) * 2 / 1e9, time.time() - t0))
 
-    def local_views(self, d: int):
-        seg = self.seg
-        n = self.w.n_participants
-        return ([self.k[d][seg[i]:seg[i + 1]] for i in range(n)], [self.v[d][seg[i]:seg[i + 1]] for i in range(n)])
+    def params(self, H: int):
+        w = self.w
+        if H not in self.p:
+            self.p[H] = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, H, torch.bfloat16)
+        return self.p[H]
 
-    def run_block(self, b: int, ev=None):
+    def sync_flags(self, H: int):
+        return [fa.fedattn_is_sync_block(H, b) for b in range(self.M)]
+
+    def flops_blocks(self, H: int):
+        w = self.w
+        fl = 4 * w.head_dim * w.n_q_heads
+        out = []
+        for b, s in enumerate(self.sync_flags(H)):
+            kt = self.keep_tok[(b // H) % len(self.keep_tok)] if (s and self.keep_tok is not None) else None
+            out.append(float(fl * visible_pairs(self.seg, s, kt)))
+        return out
+
+    def run_block(self, H: int, b: int):
         d = b % self.nd
-        k, v = self.k[d], self.v[d]
-        kc = None
-        if self.sync[b]:
-            if self.aggregate:
-                kl, vl = self.local_views(d)
-                fa.fedattn_aggregate_kv(self.p, kl, vl, self.seg, self.kg, self.vg)
-                k, v = self.kg, self.vg
-            if self.keep is not None:
-                kc = self.keep[(b // self.H) % len(self.keep)]
-        if ev is not None:
-            ev[0].record()
-        fa.fedattn_prefill(self.p, b, self.q[d], k, v, self.out[d], self.seg, keep_chunks=kc,
-                           chunk_tokens=self.w.chunk_tokens, workspace=self.ws)
-        if ev is not None:
-            ev[1].record()
+        p = self.params(H)
+        seg, n = self.seg, self.w.n_participants
+        if fa.fedattn_is_sync_block(H, b):
+            # Phase II from the participants' own matrices (views of one tensor: back to back)
+            kl = [self.k[d][seg[i]:seg[i + 1]] for i in range(n)]
+            vl = [self.v[d][seg[i]:seg[i + 1]] for i in range(n)]
+            kc = self.keep[(b // H) % len(self.keep)] if self.keep is not None else None
+            fa.fedattn_prefill_sync_local_kv(p, self.q[d], kl, vl, self.out[d], seg, keep_chunks=kc,
+                                             chunk_tokens=self.w.chunk_tokens if kc is not None else 0, workspace=self.ws)
+        else:
+            fa.fedattn_prefill(p, b, self.q[d], self.k[d], self.v[d], self.out[d], seg)
 
-    def step(self):
-        for b in range(self.M):
-            self.run_block(b)
+    def step(self, H: int, only=None):
+        """All M blocks (only = None), or the local (False) / sync (True) ones alone."""
+        for b, s in enumerate(self.sync_flags(H)):
+            if only is None or only == s:
+                self.run_block(H, b)
 
-    def batched_upper_bound(self, steps: int):
-        """All M blocks in one fedattn_prefill_blocks launch (no dependency between the blocks, no
-        aggregation): what the kernel does when launch gaps and partly filled grids are taken away."""
+    def batched_upper_bound(self, H: int, steps: int):
+        """All M blocks in one fedattn_prefill_blocks launch (no dependency between the blocks):
+        what the kernel does when launch gaps and partly filled grids are taken away."""
         if self.nd != self.M or self.keep is not None:
             return None
-        run = lambda: fa.fedattn_prefill_blocks(self.p, 0, self.M, self.q, self.k, self.v, self.out,
+        run = lambda: fa.fedattn_prefill_blocks(self.params(H), 0, self.M, self.q, self.k, self.v, self.out,
                                                 self.q[0].numel(), self.k[0].numel(), self.seg)
-        return time_region(run, steps, 2)
+        _, ms = timed_replays([run], steps, 2)
+        return float(np.median(ms)) * 1e-3
 
-    def kernel_times(self, steps: int):
-        """Average duration of the prefill kernel per block kind, HIP events around each launch."""
-        evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                for _ in range(self.M)] for _ in range(steps)]
-        device_warmup(self.step)
-        # keep the GPU busy while the host enqueues: the launches then run back to back and an
-        # event pair brackets the kernel, not the time the GPU waited for the host
-        if self.nd == self.M and self.keep is None:
-            for _ in range(max(1, steps * self.M // 20)):   # 0.7 ms of GPU work each; the host needs ~20 us per launch
-                fa.fedattn_prefill_blocks(self.p, 0, self.M, self.q, self.k, self.v, self.out,
-                                          self.q[0].numel(), self.k[0].numel(), self.seg)
-        for s in range(steps):
-            for b in range(self.M):
-                self.run_block(b, evs[s][b])
-        torch.cuda.synchronize()
-        ms = np.array([[e[0].elapsed_time(e[1]) for e in row] for row in evs])  # [steps, M]
-        return ms
+
+def prefill_leg(pb: PrefillBench, H: int, ms_step: np.ndarray, pmc_key: str | None, steps_kind: int) -> dict:
+    """Leg record for workload pb at sync interval H; ms_step: event times of the step's graph replays."""
+    w = pb.w
+    sync = pb.sync_flags(H)
+    fl = pb.flops_blocks(H)
+    fl_step = float(sum(fl))
+    med = float(np.median(ms_step))
+    tflops = fl_step / (med * 1e-3) / 1e12
+    leg = {"workload": w.name, "sync_interval": H, "blocks": pb.M, "sync_blocks": int(sum(sync)),
+           "tflop_per_step": fl_step / 1e12, "ms_per_step": med, "ms_min": float(ms_step.min()), "ms_max": float(ms_step.max()),
+           "iterations": int(ms_step.size), "value": tflops, "unit": "TFLOP/s", "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS}
+    pmc = PMC.get(pmc_key or "", {})
+    roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
+            "traffic": pmc.get("traffic_bytes"), "mfma_util": pmc.get("mfma_util"), "counters_from": pmc.get("source"),
+            "kernel": "prefill_mfma_kernel<128, *>", "launches_per_step": pb.M,
+            "flop_per_launch": fl_step / pb.M, "avg_launch_us": med * 1e3 / pb.M,
+            "timing": "HIP events around the graph replay of the step's %d launches on the replay stream, median of %d "
+                      "replays, divided by the launches (gaps between graph nodes included: the figure errs low)"
+                      % (pb.M, ms_step.size)}
+    # the two kinds of block on their own: graphs of the step's local launches and of its sync launches
+    for kind, name in ((False, "local"), (True, "sync")):
+        idx = [b for b in range(pb.M) if sync[b] == kind]
+        if not idx:
+            continue
+        g = capture(lambda: pb.step(H, only=kind), pb.out)
+        _, ms = timed_replays([g.replay], steps_kind, 1)
+        us = float(np.median(ms)) * 1e3 / len(idx)
+        roof["avg_%s_us" % name] = us
+        roof["%s_tflops" % name] = float(np.mean([fl[b] for b in idx])) / (us * 1e-6) / 1e12
+        del g
+    leg["roofline"] = roof
+    return leg
 
 
 class DecodeBench:
     """cfg4: N participants, one query each per step, all M blocks of a step through
-    fedattn_decode_blocks (one host call per step, one launch pair per block)."""
+    fedattn_decode_blocks (one host call per step, every block with its own launches)."""
 
-    def __init__(self, name: str = "cfg4_decode", n_data_blocks: int | None = None):
+    def __init__(self, name: str = "cfg4_decode"):
         self.w = fi.workload(name)
         w = self.w
         self.M = w.n_blocks
         self.seg = w.seg_offsets
-        nd = self.M if n_data_blocks is None else min(n_data_blocks, self.M)
-        assert nd == self.M, "decode keeps one cache per block resident"
         t0 = time.time()
         with ThreadPoolExecutor(max_workers=8) as ex:
-            caches = list(ex.map(lambda b: fi.decode_cache_block(w, b), range(nd)))
+            caches = list(ex.map(lambda b: fi.decode_cache_block(w, b), range(self.M)))
         self.kc = torch.stack([to_dev_bf16(c[0]) for c in caches])
         self.vc = torch.stack([to_dev_bf16(c[1]) for c in caches])
         del caches
@@ -227,16 +321,55 @@ class DecodeBench:
                                  self.seg, lens, sync_override=sync_override,
                                  workspace=self.ws_fused if fused else self.ws, fused=fused)
 
-    def timed(self, steps, sync_override: int = -1, fused: bool = False) -> float:
-        """GPU milliseconds for the given decode steps (HIP events around the whole run)."""
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        device_warmup(lambda: self.run_step(steps[0], sync_override, fused))
-        e0.record()
-        for s in steps:
-            self.run_step(s, sync_override, fused)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1)
+    def graphs(self, steps, sync_override: int = -1, fused: bool = False):
+        return [capture(lambda s=s: self.run_step(s, sync_override, fused), self.out) for s in steps]
+
+
+def decode_leg(iterations: int) -> dict:
+    db = DecodeBench()
+    w = db.w
+    all_steps = list(range(w.decode_steps))
+    t0 = time.time()
+    graphs = db.graphs(all_steps)
+    log("decode: %d step graphs captured and checked in %.1f s" % (len(graphs), time.time() - t0))
+    total_bytes = sum(db.bytes_block_step(s) * db.M for s in all_steps)
+
+    def run_all():
+        for g in graphs:
+            g.replay()
+    wall, ms = timed_replays([run_all], iterations, 1)
+    med = float(np.median(ms))
+    gbs = total_bytes / (med * 1e-3) / 1e9
+    n_launch = len(all_steps) * db.M
+    # the two kinds of block-step on their own, and the bound without launch effects, on 8 sampled steps
+    sample = sorted(set(int(s) for s in np.linspace(0, w.decode_steps - 1, 8)))
+    sample_bytes = sum(db.bytes_block_step(s) * db.M for s in sample)
+    kinds = {}
+    for name, override, fused in (("local", 0, False), ("sync", 1, False), ("blocks_fused", -1, True)):
+        gs = db.graphs(sample, override, fused)
+        _, m = timed_replays([lambda gs=gs: [g.replay() for g in gs]], max(5, iterations // 2), 1)
+        kinds[name] = float(np.median(m))
+        del gs
+    rate = lambda ms_: float(sample_bytes / (ms_ * 1e-3) / 1e9)
+    pmc = PMC["decode"]
+    return {"workload": "%s: N = %d, prompt %d, %d decoding steps x %d blocks, H = %d" % (
+                w.name, w.n_participants, db.prompt, w.decode_steps, db.M, w.sync_interval),
+            "launch": "fedattn_decode_blocks: one host call per decoding step, every block with its own launches; each "
+                      "step replayed from its own HIP graph, all %d steps in order per iteration" % len(all_steps),
+            "steps_timed": len(all_steps), "blocks": db.M, "iterations": iterations,
+            "gbytes_per_run": total_bytes / 1e9, "ms_per_run": med, "ms_per_run_wall": wall * 1e3,
+            "ms_per_decode_step": med / len(all_steps), "value": gbs, "unit": "GB/s", "frac_of_hbm_peak": gbs / PEAK_HBM_GBS,
+            "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                         "traffic": pmc.get("traffic_bytes"), "counters_from": pmc.get("source"),
+                         "kernel": "decode_stream_kernel (+ decode_combine_kernel in sync blocks)",
+                         "bytes_per_block_step": total_bytes / n_launch, "avg_block_step_us": med * 1e3 / n_launch,
+                         "timing": "HIP events around %d graph replays (all steps of the run), median of %d runs, divided by "
+                                   "the block-steps (gaps between launches included)" % (len(all_steps), iterations),
+                         "local_GBps": rate(kinds["local"]), "sync_GBps": rate(kinds["sync"]),
+                         "avg_local_us": kinds["local"] * 1e3 / (len(sample) * db.M),
+                         "avg_sync_us": kinds["sync"] * 1e3 / (len(sample) * db.M),
+                         "blocks_fused_GBps": rate(kinds["blocks_fused"]),
+                         "kinds_measured_on_steps": sample}}
 
 
 def end_to_end_leg(steps: int) -> dict:
@@ -265,7 +398,8 @@ def end_to_end_leg(steps: int) -> dict:
             kc = keep[b // w.sync_interval] if sync[b] else None
             block_forward(p, b, x, weights[b], seg, buf, keep_chunks=kc, chunk_tokens=w.chunk_tokens if kc is not None else 0)
 
-    sec = time_region(forward, steps, 1)
+    _, ms = timed_replays([forward], steps, 1)
+    sec = float(np.median(ms)) * 1e-3
     fl_attn = 0.0
     for b in range(w.n_blocks):
         kt = keep_tokens(fi.keep_chunks(w, b // w.sync_interval), seg, w.chunk_tokens) if sync[b] else None
@@ -277,62 +411,13 @@ def end_to_end_leg(steps: int) -> dict:
             "tflops_all": (fl_attn + fl_gemm) / sec / 1e12, "finite": bool(torch.isfinite(x).all().item())}
 
 
-DEVICE_WARMUP_S = 0.3
-
-
-def device_warmup(fn, seconds: float = DEVICE_WARMUP_S) -> None:
-    """Untimed work before a measurement: the GPU raises its clock over the first tenths of a
-    second of sustained load (the headline step measured 0.90 ms right after idle and 0.84 ms
-    from 0.2 s on), and a throughput figure should be the sustained one."""
-    t0 = time.perf_counter()
-    while time.perf_counter() - t0 < seconds:
-        for _ in range(8):
-            fn()
-        torch.cuda.synchronize()
-
-
-def time_region(fn, steps: int, warmup: int) -> float:
-    device_warmup(fn)
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        fn()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
-
-
-def capture_step(pb: "PrefillBench"):
-    """One step (every launch of it) captured into a HIP graph, so that the timed region
-    measures the GPU and not the Python loop around 40 launches of 20-50 us each.  The replay
-    is checked against the eager step before it is used."""
-    pb.step()
-    torch.cuda.synchronize()
-    ref = pb.out.clone()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.stream(side):
-        with torch.cuda.graph(graph, stream=side):
-            pb.step()
-    torch.cuda.synchronize()
-    for rep in range(2):
-        pb.out.zero_()
-        graph.replay()
-        torch.cuda.synchronize()
-        if not torch.equal(pb.out, ref):
-            raise RuntimeError("graph replay %d of the step differs from the eager step" % rep)
-    return graph
-
-
-def cpu_baseline(pb: PrefillBench, budget_s: float = 12.0) -> dict:
+def cpu_baseline(w, H: int, budget_s: float = 12.0) -> dict:
     """The oracle, as it stands, on a bounded sample of the headline workload."""
     import oracle
-    w = pb.w
-    q, k, v = fi.prefill_block(w, 3)
-    seg = pb.seg
-    sync = oracle.is_sync_block(pb.H, 3)
+    block = 3
+    q, k, v = fi.prefill_block(w, block)
+    seg = w.seg_offsets
+    sync = oracle.is_sync_block(H, block)
     rows, heads = fi.sample_rows(seg, w.n_q_heads, 256, fi.DEFAULT_SEED, salt=77)
     rows, heads = rows[-256:], heads[-256:]
 
@@ -359,26 +444,22 @@ def cpu_baseline(pb: PrefillBench, budget_s: float = 12.0) -> dict:
             break
     flops = 4.0 * w.head_dim * n_pairs
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.n_threads(), "kind": "oracle",
-            "sample": "%d random (row, head) pairs of block 3 (%s) of %s, fp64, %.1f s"
-                      % (n_rows, "sync" if sync else "local", w.name, dt)}
+            "sample": "%d random (row, head) pairs of block %d (%s at H = %d) of %s, fp64, %.1f s"
+                      % (n_rows, block, "sync" if sync else "local", H, w.name, dt)}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2_llama8b_prefill",
-                    choices=["cfg2_llama8b_prefill", "cfg3_hetero_prefill", "cfg5_sparse_sync"])
-    ap.add_argument("--sync-interval", type=int, default=None, help="override H of the workload")
-    ap.add_argument("--no-aggregate", action="store_true", help="skip fedattn_aggregate_kv in sync blocks")
-    ap.add_argument("--no-decode", action="store_true", help="skip the decode measurement")
-    ap.add_argument("--no-graph", action="store_true", help="time the step launched from Python, not a graph replay")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--legs", default="cfg3,cfg5,cfg2,decode",
+                    help="comma-separated: cfg3 (the H sweep), cfg3_H1|H4|H8|H32 (one H), cfg5, cfg2, decode")
     ap.add_argument("--end-to-end", action="store_true",
                     help="also run the 8-block mini-Transformer of the end-to-end configuration (adds ~20 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--decode-steps", type=int, default=8, help="decode steps timed (spread over the 256)")
-    ap.add_argument("--data-blocks", type=int, default=None, help="distinct input blocks kept resident")
+    ap.add_argument("--decode-iterations", type=int, default=20, help="timed passes over the 256 decoding steps")
+    ap.add_argument("--data-blocks", type=int, default=None, help="distinct input blocks kept resident (large workloads)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (participants are segments of one batch); "
@@ -388,116 +469,118 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     fa.load()
+    legs_req = [x.strip() for x in args.legs.split(",") if x.strip()]
+    legs = {}
+    headline = None
+    cpu = None
+    cost = None
 
-    nd = args.data_blocks
-    if nd is None and args.workload != "cfg2_llama8b_prefill":
-        nd = 4   # 336 MB (cfg3) / 0.8 GB (cfg5) of inputs per block: keep a few distinct ones
-    pb = PrefillBench(args.workload, nd, args.sync_interval, aggregate=not args.no_aggregate)
-    for _ in range(2):
-        pb.step()   # first launches set kernel attributes; keep that out of the capture
-    sec_eager = time_region(pb.step, args.steps, args.warmup)
-    if args.no_graph:
-        sec = sec_eager
-    else:
-        graph = capture_step(pb)
-        sec = time_region(graph.replay, args.steps, args.warmup)
-    tflops = pb.flops_step / sec / 1e12
-    log("%s: %.3f ms/step, %.1f useful TFLOP/s (%s; launched from Python: %.3f ms/step)"
-        % (pb.w.name, sec * 1e3, tflops, "eager" if args.no_graph else "HIP graph replay", sec_eager * 1e3))
+    cfg3_hs = []
+    for name in legs_req:
+        if name == "cfg3":
+            cfg3_hs = list(CFG3_SWEEP)
+        elif name.startswith("cfg3_H"):
+            cfg3_hs.append(int(name[6:]))
+    if cfg3_hs:
+        pb = PrefillBench("cfg3_hetero_prefill", args.data_blocks or 4)
+        graphs = [capture(lambda H=H: pb.step(H), pb.out) for H in cfg3_hs]
+        wall, ms = timed_replays([g.replay for g in graphs], args.steps, args.warmup)
+        fl_sweep = sum(sum(pb.flops_blocks(H)) for H in cfg3_hs)
+        tflops = fl_sweep / wall / 1e12
+        n_launch = pb.M * len(cfg3_hs)
+        ev_ms = float(np.median(ms.sum(axis=1)))
+        log("cfg3 H in %s: %.2f ms per step (events %.2f ms), %.1f useful TFLOP/s" % (cfg3_hs, wall * 1e3, ev_ms, tflops))
+        for i, H in enumerate(cfg3_hs):
+            legs["cfg3_H%d" % H] = prefill_leg(pb, H, ms[:, i], "cfg3_H%d" % H, max(3, args.steps // 4))
+            log("  cfg3 H=%d: %.2f ms, %.1f TFLOP/s (%.1f%% of peak)" % (H, legs["cfg3_H%d" % H]["ms_per_step"],
+                legs["cfg3_H%d" % H]["value"], 100 * legs["cfg3_H%d" % H]["frac_of_bf16_peak"]))
+        pmc = PMC.get("cfg3_H4", {})
+        achieved = fl_sweep / (ev_ms * 1e-3) / 1e12
+        headline = {
+            "value": tflops, "ms_per_step": wall * 1e3,
+            "config": {"workload": "cfg3_hetero_prefill: N = 8 participants, segment lengths %s (U[1024, 3072] from the seed), "
+                                   "M = 32 blocks, 32/8 heads of 128, bf16; one step = the configuration's sweep H in %s, "
+                                   "%d launches" % (list(pb.w.seg_lens), cfg3_hs, n_launch),
+                       "participants": pb.w.n_participants, "seg_lens": [int(x) for x in pb.w.seg_lens], "blocks": pb.M,
+                       "sync_intervals": cfg3_hs, "q_heads": pb.w.n_q_heads, "kv_heads": pb.w.n_kv_heads,
+                       "head_dim": pb.w.head_dim, "tflop_per_step": fl_sweep / 1e12,
+                       "launch": "one launch per block: fedattn_prefill (local blocks), fedattn_prefill_sync_local_kv (sync "
+                                 "blocks, K/V read in place); each H's 32 launches replayed from a HIP graph",
+                       "distinct_input_blocks": pb.nd, "untimed_device_warmup_s": DEVICE_WARMUP_S},
+            "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                         "frac": achieved / PEAK_BF16_TFLOPS, "traffic": pmc.get("traffic_bytes"),
+                         "mfma_util": pmc.get("mfma_util"), "counters_from": pmc.get("source"),
+                         "kernel": "prefill_mfma_kernel<128, 1>", "launches_per_step": n_launch,
+                         "flop_per_launch": fl_sweep / n_launch, "avg_launch_us": ev_ms * 1e3 / n_launch,
+                         "timing": "HIP events around every graph replay of the timed steps on the replay stream, median over "
+                                   "%d steps of the step's total, divided by its %d launches" % (args.steps, n_launch)}}
+        Hc = 4 if 4 in cfg3_hs else cfg3_hs[0]
+        cost = cost_report(pb.w.seg_lens, pb.sync_flags(Hc), pb.w.n_q_heads, pb.w.n_kv_heads, pb.w.head_dim).as_dict()
+        cost["sync_interval"] = Hc
+        if not args.no_cpu_baseline:
+            cpu = cpu_baseline(pb.w, Hc)
+            log("cpu oracle: %.5f TFLOP/s on %d threads" % (cpu["value"], cpu["cores"]))
+        del graphs, pb
+        torch.cuda.empty_cache()
 
-    # dominant kernel: HIP events around every prefill launch, same steps again
-    ms = pb.kernel_times(min(args.steps, 10))
-    kern_ms = ms.sum(axis=1).mean()
-    achieved = pb.flops_step / (kern_ms * 1e-3) / 1e12
-    sync_idx = [b for b in range(pb.M) if pb.sync[b]]
-    loc_idx = [b for b in range(pb.M) if not pb.sync[b]]
-    roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(pb.w.name),
-            "kernel": "prefill_mfma_kernel<128>", "launches_per_step": pb.M,
-            "avg_launch_us": float(ms.mean() * 1e3),
-            "avg_local_us": float(ms[:, loc_idx].mean() * 1e3) if loc_idx else None,
-            "avg_sync_us": float(ms[:, sync_idx].mean() * 1e3) if sync_idx else None,
-            "local_tflops": (np.mean([pb.flops_block[b] for b in loc_idx]) / (ms[:, loc_idx].mean() * 1e-3) / 1e12)
-            if loc_idx else None,
-            "sync_tflops": (np.mean([pb.flops_block[b] for b in sync_idx]) / (ms[:, sync_idx].mean() * 1e-3) / 1e12)
-            if sync_idx else None}
-    log("prefill kernel: avg %.1f us/launch -> %.1f TFLOP/s (%.1f%% of bf16 MFMA peak)"
-        % (roof["avg_launch_us"], achieved, 100 * roof["frac"]))
+    for name, wl, nd, steps, pmc_key in (("cfg5", "cfg5_sparse_sync", args.data_blocks or 4, args.steps, "cfg5"),
+                                         ("cfg2", "cfg2_llama8b_prefill", None, max(args.steps, 100), "cfg2")):
+        if name not in legs_req:
+            continue
+        pb = PrefillBench(wl, nd)
+        H = pb.w.sync_interval
+        g = capture(lambda: pb.step(H), pb.out)
+        wall, ms = timed_replays([g.replay], steps, args.warmup)
+        legs[name] = prefill_leg(pb, H, ms[:, 0], pmc_key, max(3, steps // 4))
+        if name == "cfg2":
+            b = pb.batched_upper_bound(H, 10)
+            if b is not None:
+                legs[name]["roofline"]["blocks_batched_ms"] = b * 1e3
+                legs[name]["roofline"]["blocks_batched_tflops"] = sum(pb.flops_blocks(H)) / b / 1e12
+        log("%s: %.3f ms per step, %.1f TFLOP/s (%.1f%% of peak)" % (name, legs[name]["ms_per_step"], legs[name]["value"],
+                                                                     100 * legs[name]["frac_of_bf16_peak"]))
+        if headline is None:
+            headline = {"value": legs[name]["value"], "ms_per_step": wall * 1e3,
+                        "config": {"workload": wl, "sync_interval": H}, "roofline": legs[name]["roofline"]}
+            if not args.no_cpu_baseline and cpu is None:
+                cpu = cpu_baseline(pb.w, H)
+        del g, pb
+        torch.cuda.empty_cache()
 
-    batched = pb.batched_upper_bound(min(args.steps, 10))
-    if batched is not None:
-        roof["blocks_batched_tflops"] = pb.flops_step / batched / 1e12
-        roof["blocks_batched_ms"] = batched * 1e3
-        log("all %d blocks in one launch (upper bound, no block dependencies): %.3f ms, %.1f TFLOP/s"
-            % (pb.M, batched * 1e3, roof["blocks_batched_tflops"]))
+    decode = None
+    if "decode" in legs_req:
+        decode = decode_leg(args.decode_iterations)
+        log("decode: %.0f GB/s over %d steps x %d blocks (%.1f%% of HBM peak; local block-steps %.0f, sync %.0f, "
+            "blocks sharing launches %.0f GB/s)" % (decode["value"], decode["steps_timed"], decode["blocks"],
+            100 * decode["frac_of_hbm_peak"], decode["roofline"]["local_GBps"], decode["roofline"]["sync_GBps"],
+            decode["roofline"]["blocks_fused_GBps"]))
+        torch.cuda.empty_cache()
 
-    # the paper's analytic cost figures for this plan (Section VII-A, evaluation metrics)
-    cost = cost_report(pb.w.seg_lens, pb.sync, pb.w.n_q_heads, pb.w.n_kv_heads, pb.w.head_dim,
-                       keep_fraction=pb.w.keep_fraction if pb.w.chunk_tokens else 1.0)
+    if headline is None and decode is not None:
+        headline = {"value": decode["value"], "ms_per_step": decode["ms_per_run"], "config": {"workload": decode["workload"]},
+                    "roofline": decode["roofline"], "unit": "GB/s"}
+    if headline is None:
+        print("bench.py: no leg selected", file=sys.stderr)
+        return 2
 
     result = {"metric": "prefill attn TFLOP/s (% bf16 MFMA peak); decode HBM GB/s (% peak)",
-              "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-              "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-              "dtype": "bf16", "data": "synthetic",
-              "config": {"workload": pb.w.name, "participants": pb.w.n_participants,
-                         "seg_lens": [int(x) for x in pb.w.seg_lens], "blocks": pb.M, "sync_interval": pb.H,
-                         "q_heads": pb.w.n_q_heads, "kv_heads": pb.w.n_kv_heads, "head_dim": pb.w.head_dim,
-                         "launch": ("one fedattn_prefill per block, fedattn_aggregate_kv before each sync block"
-                                    if pb.aggregate else "one fedattn_prefill per block")
-                                   + ("" if args.no_graph else "; the step's launches replayed from a HIP graph"),
-                         "ms_per_step_launched_from_python": sec_eager * 1e3,
-                         "untimed_device_warmup_s": DEVICE_WARMUP_S},
-              "frac_of_bf16_peak": tflops / PEAK_BF16_TFLOPS,
-              "roofline": roof,
-              "analytic_cost_per_participant": cost.as_dict()}
-
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(pb)
-        log("cpu oracle: %.5f TFLOP/s on %d threads" % (result["cpu_baseline"]["value"], result["cpu_baseline"]["cores"]))
-    del pb
-    torch.cuda.empty_cache()
-
-    if not args.no_decode:
-        db = DecodeBench()
-        steps = sorted(set(int(s) for s in np.linspace(0, db.w.decode_steps - 1, args.decode_steps)))
-        device_warmup(lambda: db.run_step(steps[0]))
-        t0 = time.perf_counter()
-        for s in steps:
-            db.run_step(s)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        total_bytes = sum(db.bytes_block_step(s) * db.M for s in steps)
-        ms_all = db.timed(steps)
-        ms_loc = db.timed(steps, 0)     # every block forced local: the local-block kernels alone
-        ms_syn = db.timed(steps, 1)     # every block forced sync
-        ms_fused = db.timed(steps, -1, fused=True)   # upper bound: the blocks of a kind share launches
-        gbs = lambda ms: float(total_bytes / (ms * 1e-3) / 1e9)
-        n_launch = len(steps) * db.M
-        dec = {"workload": db.w.name, "steps_timed": steps, "blocks": db.M,
-               "launch": "fedattn_decode_blocks: one host call per step; local blocks one launch each (chunks merged "
-                         "in the streaming kernel), sync blocks a split-KV + combine launch pair",
-               "end_to_end_GBps": total_bytes / wall / 1e9,
-               "ms_per_decode_step": wall / len(steps) * 1e3,
-               "roofline": {"bound": "hbm", "achieved": gbs(ms_all), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                            "frac": gbs(ms_all) / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(db.w.name),
-                            "kernel": "decode_stream_kernel + decode_combine_kernel (per block-step, HIP events)",
-                            "avg_block_step_us": ms_all * 1e3 / n_launch,
-                            "local_GBps": gbs(ms_loc), "sync_GBps": gbs(ms_syn),
-                            "avg_local_us": ms_loc * 1e3 / n_launch, "avg_sync_us": ms_syn * 1e3 / n_launch,
-                            "blocks_fused_GBps": gbs(ms_fused), "blocks_fused_ms_per_step": ms_fused / len(steps)}}
-        result["decode"] = dec
-        log("decode: %.0f GB/s by events (all-local %.0f, all-sync %.0f), %.0f GB/s end to end; "
-            "upper bound with the blocks of a kind sharing launches (no block dependencies): %.0f GB/s"
-            % (dec["roofline"]["achieved"], dec["roofline"]["local_GBps"], dec["roofline"]["sync_GBps"],
-               dec["end_to_end_GBps"], dec["roofline"]["blocks_fused_GBps"]))
-
+              "value": headline["value"], "unit": headline.get("unit", "TFLOP/s"), "n_gpus": 1, "steps": args.steps,
+              "warmup": args.warmup, "ms_per_step": headline["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "config": headline["config"],
+              "frac_of_bf16_peak": headline["value"] / PEAK_BF16_TFLOPS if headline.get("unit", "TFLOP/s") == "TFLOP/s" else None,
+              "roofline": headline["roofline"], "legs": legs}
+    if decode is not None:
+        result["decode"] = decode
+    if cost is not None:
+        result["analytic_cost_per_participant"] = cost
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     if args.end_to_end:
         torch.cuda.empty_cache()
         result["end_to_end"] = end_to_end_leg(3)
         log("end to end: %.1f ms per 8-block forward (%.2f TFLOP attention + %.2f TFLOP GEMM -> %.0f TFLOP/s)"
             % (result["end_to_end"]["ms_per_forward"], result["end_to_end"]["attention_tflop"],
                result["end_to_end"]["gemm_tflop"], result["end_to_end"]["tflops_all"]))
-
     print(json.dumps(result))
     return 0
 
