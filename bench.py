@@ -394,9 +394,13 @@ def end_to_end_leg(steps: int) -> dict:
 
     def forward():
         x.copy_(x0)
+        pending = None
         for b in range(w.n_blocks):
             kc = keep[b // w.sync_interval] if sync[b] else None
-            block_forward(p, b, x, weights[b], seg, buf, keep_chunks=kc, chunk_tokens=w.chunk_tokens if kc is not None else 0)
+            pending = block_forward(p, b, x, weights[b], seg, buf, keep_chunks=kc,
+                                    chunk_tokens=w.chunk_tokens if kc is not None else 0, pending=pending,
+                                    defer_update=True)["pending"]
+        fa.fedattn_residual_add(x, pending)
 
     _, ms = timed_replays([forward], steps, 1)
     sec = float(np.median(ms)) * 1e-3

@@ -252,8 +252,7 @@ FEDATTN_API fedattn_status fedattn_aggregate_kv(const fedattn_params* params, co
  * connection and a normalisation: Section III-B; the local forward of Section IV-B):
  *   x += W_O Attention(RoPE(RMSNorm(x) W_QKV));  x += W_down (silu(gate) * up),
  *   [gate up] = RMSNorm(x) W_gate_up.
- * The matrix products are plain GEMMs and stay with the caller; these four passes are the
- * rest.  Residual stream x in fp32, every other tensor bf16, all device pointers, 16-byte
+ * The matrix products are plain GEMMs and stay with the caller; these passes are the rest.  Residual stream x in fp32, every other tensor bf16, all device pointers, 16-byte
  * aligned, contiguous rows.
  *
  * fedattn_rmsnorm: out[r] = bf16(x[r] / sqrt(mean_j x[r][j]^2 + eps)), unit gain;
@@ -266,6 +265,10 @@ FEDATTN_API fedattn_status fedattn_aggregate_kv(const fedattn_params* params, co
  * fedattn_swiglu: out[r][f] = bf16(silu(gate_up[r][f]) * gate_up[r][hidden + f]);
  *   gate_up bf16 [rows, 2 hidden], out bf16 [rows, hidden]; hidden a multiple of 8.
  * fedattn_residual_add: x[i] += y[i]; x fp32, y bf16, n elements (a multiple of 4).
+ * fedattn_residual_add_rmsnorm: fedattn_residual_add(x, y) followed by fedattn_rmsnorm(x, out) in
+ *   one pass over the residual stream (the update that closes one half of a block and the
+ *   normalisation that opens the next); same results as the two calls.  x fp32 [rows, d_model]
+ *   updated in place, y bf16 [rows, d_model], out bf16 [rows, d_model].
  */
 FEDATTN_API fedattn_status fedattn_rmsnorm(const float* x, void* out, int64_t rows, int32_t d_model, float eps, void* stream);
 FEDATTN_API fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens,
@@ -273,6 +276,8 @@ FEDATTN_API fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t
                                       void* stream);
 FEDATTN_API fedattn_status fedattn_swiglu(const void* gate_up, void* out, int64_t rows, int32_t hidden, void* stream);
 FEDATTN_API fedattn_status fedattn_residual_add(float* x, const void* y, int64_t n, void* stream);
+FEDATTN_API fedattn_status fedattn_residual_add_rmsnorm(float* x, const void* y, void* out, int64_t rows, int32_t d_model,
+                                            float eps, void* stream);
 
 /* Reason of the calling thread's most recent failure ("" if none). */
 FEDATTN_API const char* fedattn_last_error(void);

@@ -27,6 +27,7 @@ EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill"
            "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_decode_blocks_fused",
            "fedattn_decode_static", "fedattn_aggregate_kv",
            "fedattn_rmsnorm", "fedattn_rope_split_qkv", "fedattn_swiglu", "fedattn_residual_add",
+           "fedattn_residual_add_rmsnorm",
            "fedattn_last_error", "fedattn_version")
 
 
@@ -86,6 +87,8 @@ def load():
     lib.fedattn_swiglu.restype = ctypes.c_int
     lib.fedattn_residual_add.argtypes = [vp, vp, i64, vp]
     lib.fedattn_residual_add.restype = ctypes.c_int
+    lib.fedattn_residual_add_rmsnorm.argtypes = [vp, vp, vp, i64, i32, fl, vp]
+    lib.fedattn_residual_add_rmsnorm.restype = ctypes.c_int
     lib.fedattn_last_error.restype = ctypes.c_char_p
     lib.fedattn_version.restype = ctypes.c_char_p
     _lib = lib
@@ -319,3 +322,12 @@ def fedattn_residual_add(x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
     if x.dtype != torch.float32 or y.dtype != torch.bfloat16 or x.shape != y.shape:
         raise TypeError("residual_add: x fp32, y bf16, same shape")
     _check(load().fedattn_residual_add(_dev(x, "x"), _dev(y, "y"), x.numel(), _stream(stream)))
+
+
+def fedattn_residual_add_rmsnorm(x: torch.Tensor, y: torch.Tensor, out: torch.Tensor, eps: float = 1e-6, stream=None) -> None:
+    """x fp32 += y bf16, then out bf16 = rmsnorm(x), one pass; all [rows, d_model]."""
+    if x.dtype != torch.float32 or y.dtype != torch.bfloat16 or out.dtype != torch.bfloat16 or x.dim() != 2 \
+            or x.shape != y.shape or x.shape != out.shape:
+        raise TypeError("residual_add_rmsnorm: x fp32, y and out bf16, all [rows, d_model]")
+    _check(load().fedattn_residual_add_rmsnorm(_dev(x, "x"), _dev(y, "y"), _dev(out, "out"), x.shape[0], x.shape[1],
+                                               float(eps), _stream(stream)))

@@ -632,6 +632,20 @@ fedattn_status fedattn_rmsnorm(const float* x, void* out, int64_t rows, int32_t 
   return FEDATTN_OK;
 }
 
+fedattn_status fedattn_residual_add_rmsnorm(float* x, const void* y, void* out, int64_t rows, int32_t d_model, float eps,
+                                            void* stream) {
+  if (rows < 0 || d_model <= 0 || d_model % 4 != 0)
+    return fail(FEDATTN_EINVAL, "residual_add_rmsnorm: rows >= 0, d_model a positive multiple of 4");
+  if (!(eps >= 0.f)) return fail(FEDATTN_EINVAL, "residual_add_rmsnorm: eps must be non-negative");
+  if (rows == 0) return FEDATTN_OK;
+  if (!x || !y || !out || !aligned16(x) || !aligned16(y) || !aligned16(out))
+    return fail(FEDATTN_EINVAL, "residual_add_rmsnorm: x, y and out must be non-NULL and 16-byte aligned");
+  if ((rows + 3) / 4 > kMaxGrid) return fail(FEDATTN_EUNSUPPORTED, "residual_add_rmsnorm: too many rows");
+  hipError_t e = launch_residual_add_rmsnorm(x, y, out, rows, d_model, eps, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(FEDATTN_ELAUNCH, "residual_add_rmsnorm: %s", hipGetErrorString(e));
+  return FEDATTN_OK;
+}
+
 fedattn_status fedattn_rope_split_qkv(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens,
                                       int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float theta,
                                       void* stream) {

@@ -1,7 +1,7 @@
 // The element-wise pieces of the decoder block around the attention operator in the
 // end-to-end configuration: RMSNorm, rotary position embedding (with the split of the
-// fused QKV projection into the attention's q, k, v tensors), SwiGLU and the residual
-// add.  The block structure is the paper's (Section III-B: attention and a feed-forward
+// fused QKV projection into the attention's q, k, v tensors), SwiGLU, the residual add, and
+// the residual add fused into the RMSNorm that follows it.  The block structure is the paper's (Section III-B: attention and a feed-forward
 // network, each with a residual connection and a normalisation; Section IV-B local
 // forward); the Llama-style variants are those of the configuration.  All four are
 // bandwidth-bound passes: 16-byte accesses with the nontemporal hint (every element is touched
@@ -25,12 +25,18 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 }
 
 // out[r] = bf16(x[r] / sqrt(mean(x[r]^2) + eps)); one wavefront per row, 4 rows per workgroup.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, uint16_t* __restrict__ out,
-                                                      int64_t rows, int d_model, float eps) {
+// ADD: the residual update of the previous half of the block is applied on the way,
+// x[r] += y[r] (y bf16), and the updated row is written back: one pass over the fp32 stream
+// where the separate residual-add and RMSNorm kernels take two (12 instead of 16 bytes per
+// element; same arithmetic in the same order, so the results are those of the two kernels).
+template <bool ADD>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const uint16_t* __restrict__ y,
+                                                      uint16_t* __restrict__ out, int64_t rows, int d_model, float eps) {
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
-  const f32x4* xr = reinterpret_cast<const f32x4*>(x + r * d_model);
+  f32x4* xr = reinterpret_cast<f32x4*>(x + r * d_model);
+  const u32x2_t* yr = reinterpret_cast<const u32x2_t*>(y + (ADD ? r * d_model : 0));
   const int n4 = d_model / 4;
   u32x2_t* orow = reinterpret_cast<u32x2_t*>(out + r * d_model);
   float ss = 0.f;
@@ -38,14 +44,26 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   constexpr int kHeld = 16;
   if (n4 <= kHeld * 64) {
     f32x4 held[kHeld];
+    u32x2_t upd[ADD ? kHeld : 1];
 #pragma unroll
     for (int j = 0; j < kHeld; ++j) {
       const int i = lane + 64 * j;
       held[j] = i < n4 ? __builtin_nontemporal_load(xr + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (ADD) upd[j] = i < n4 ? __builtin_nontemporal_load(yr + i) : u32x2_t{0u, 0u};
     }
 #pragma unroll
     for (int j = 0; j < kHeld; ++j) {
-      const f32x4 v = held[j];
+      f32x4 v = held[j];
+      if constexpr (ADD) {
+        const f32x2 y0 = bf16_pair(upd[j][0]), y1 = bf16_pair(upd[j][1]);
+        v[0] += y0[0];
+        v[1] += y0[1];
+        v[2] += y1[0];
+        v[3] += y1[1];
+        held[j] = v;
+        const int i = lane + 64 * j;
+        if (i < n4) __builtin_nontemporal_store(v, xr + i);
+      }
       ss += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
     }
     ss = wave_sum(ss);
@@ -59,7 +77,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     return;
   }
   for (int i = lane; i < n4; i += 64) {
-    const f32x4 v = xr[i];
+    f32x4 v = xr[i];
+    if constexpr (ADD) {
+      const u32x2_t u = yr[i];
+      const f32x2 y0 = bf16_pair(u[0]), y1 = bf16_pair(u[1]);
+      v[0] += y0[0];
+      v[1] += y0[1];
+      v[2] += y1[0];
+      v[3] += y1[1];
+      xr[i] = v;   // read back below by the same lane
+    }
     ss += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
   }
   ss = wave_sum(ss);
@@ -159,8 +186,16 @@ __global__ __launch_bounds__(256) void residual_add_kernel(float* __restrict__ x
 
 hipError_t launch_rmsnorm(const float* x, void* out, int64_t rows, int d_model, float eps, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, reinterpret_cast<uint16_t*>(out),
-                     rows, d_model, eps);
+  hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, const_cast<float*>(x),
+                     static_cast<const uint16_t*>(nullptr), reinterpret_cast<uint16_t*>(out), rows, d_model, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_residual_add_rmsnorm(float* x, const void* y, void* out, int64_t rows, int d_model, float eps,
+                                       hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x,
+                     reinterpret_cast<const uint16_t*>(y), reinterpret_cast<uint16_t*>(out), rows, d_model, eps);
   return hipGetLastError();
 }
 

@@ -53,8 +53,11 @@ struct PrefillArgs {
   float scale;              // softmax scale
   int32_t n_ordered;        // > 0: one workgroup per query tile, workgroup p takes tile_order[p] (MFMA kernel)
   int32_t warm_kv;          // MFMA kernel: every workgroup pulls the K, V rows of its own query rows into L2 first
+  int32_t one_tile_heavy_first;  // MFMA kernel, causal launch of several rounds of workgroups: one query tile per
+                                 // workgroup, heaviest first (seg.pair_cum then counts tiles in seg_order's order)
   SegLayout seg;
   uint16_t tile_order[kMaxOrderedTiles];
+  uint8_t seg_order[kMaxP];      // participants by decreasing length (local blocks of a heavy-first launch)
 };
 
 static_assert(sizeof(PrefillArgs) <= 4096, "kernel arguments are limited to 4 KB");
@@ -109,6 +112,8 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, int n_z, hipStream_t s)
 hipError_t launch_decode_zero_counters(int32_t* counters, int n, int slices, int64_t slice_bytes, hipStream_t s);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t s);
 hipError_t launch_rmsnorm(const float* x, void* out, int64_t rows, int d_model, float eps, hipStream_t s);
+hipError_t launch_residual_add_rmsnorm(float* x, const void* y, void* out, int64_t rows, int d_model, float eps,
+                                       hipStream_t s);
 hipError_t launch_rope_split(const void* qkv, const int32_t* pos, void* q, void* k, void* v, int64_t tokens, int Hq,
                              int Hkv, int D, float theta, hipStream_t s);
 hipError_t launch_swiglu(const void* gate_up, void* out, int64_t rows, int F, hipStream_t s);

@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
   const Tab seg_tab = load_tab(a.seg.seg_off);
   const Tab tile_tab = load_tab(a.seg.tile_cum);
   const Tab pair_tab = load_tab(a.seg.pair_cum);
+  const int order_lo = a.seg_order[lane], order_hi = a.seg_order[lane + 64];
 
   // workgroup -> (kv head, head subgroup, query tile pair); kv head fastest so that the
   // workgroups of one KV head land on one XCD (8 XCDs, round-robin dispatch) and its
@@ -121,6 +122,21 @@ __global__ __launch_bounds__(256 * NG, 2) void prefill_mfma_kernel(PrefillArgs a
   } else if (!causal) {
     if (p >= T) return;
     tile_a = T - 1 - p;
+  } else if (a.one_tile_heavy_first) {
+    // A launch of several rounds of workgroups: equal-sized pairs would all finish together and
+    // leave the last round partly empty.  One tile per workgroup instead, dispatched heaviest
+    // first, so that the short walks at the end of the list fill the gaps.  Sync block: work
+    // grows with the position in the sequence.  Local block: the participants in order of
+    // decreasing length, each one's tiles from its last to its first.
+    if (p >= T) return;
+    if (is_sync) {
+      tile_a = T - 1 - p;
+    } else {
+      const int s = tab_find(pair_tab, p);   // position in the length order
+      const int pi = p - tab_at(pair_tab, s);
+      const int n = s < 64 ? __builtin_amdgcn_readlane(order_lo, s) : __builtin_amdgcn_readlane(order_hi, s - 64);
+      tile_a = tab_at(tile_tab, n + 1) - 1 - pi;
+    }
   } else if (is_sync) {
     if (p >= (T + 1) / 2) return;
     tile_a = T - 1 - p;
@@ -615,6 +631,27 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a_in, int n_blocks, hipStream_
       wg_tiles = cnt;
       grid.x = (unsigned)(wg_tiles * per_tile);
     }
+  }
+  // More than one round of 4-wave workgroups (two per CU): one query tile per workgroup, heaviest first.
+  if (!wide && n_blocks == 1 && a.causal && a.n_ordered == 0 && (int64_t)grid.x > 2 * (int64_t)a.n_cus) {
+    const bool is_sync = a.sync_override >= 0 ? a.sync_override != 0 : sync_block_rule(a.sync_interval, a.block_idx0);
+    a.one_tile_heavy_first = 1;
+    if (!is_sync) {
+      const int N = a.seg.n;
+      int order[kMaxP];
+      for (int n = 0; n < N; ++n) order[n] = n;
+      std::stable_sort(order, order + N, [&](int x, int y) {
+        return a.seg.tile_cum[x + 1] - a.seg.tile_cum[x] > a.seg.tile_cum[y + 1] - a.seg.tile_cum[y];
+      });
+      int run = 0;
+      for (int i = 0; i < N; ++i) {
+        a.seg_order[i] = (uint8_t)order[i];
+        a.seg.pair_cum[i] = run;
+        run += a.seg.tile_cum[order[i] + 1] - a.seg.tile_cum[order[i]];
+      }
+      a.seg.pair_cum[N] = run;
+    }
+    grid.x = (unsigned)(a.n_q_tiles * per_tile);
   }
   if (a.D == 128) return wide ? launch_prefill_mfma_t<128, 2>(a, grid, s) : launch_prefill_mfma_t<128, 1>(a, grid, s);
   return wide ? launch_prefill_mfma_t<64, 2>(a, grid, s) : launch_prefill_mfma_t<64, 1>(a, grid, s);

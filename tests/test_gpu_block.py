@@ -87,6 +87,48 @@ def test_swiglu_and_residual_kernels():
     assert np.array_equal(tx.cpu().numpy(), x + y), "fp32 residual add must be exactly rounded"
 
 
+def test_residual_add_fused_into_rmsnorm_equals_the_two_kernels():
+    g = np.random.default_rng(4)
+    for rows, d in ((37, 2048), (5, 96), (6, 4096), (3, 4100), (2, 8192)):     # held in registers / two passes
+        x = (g.standard_normal((rows, d)) * 3).astype(np.float32)
+        y = fi.round_to_bf16(g.standard_normal((rows, d)).astype(np.float32))
+        ty = dev(y, BF16)
+        x_two, x_one = torch.from_numpy(x).cuda(), torch.from_numpy(x).cuda()
+        h_two = torch.full((rows, d), float("nan"), dtype=BF16, device="cuda")
+        h_one = torch.full_like(h_two, float("nan"))
+        say("residual add + rmsnorm %dx%d" % (rows, d))
+        fa.fedattn_residual_add(x_two, ty)
+        fa.fedattn_rmsnorm(x_two, h_two)
+        fa.fedattn_residual_add_rmsnorm(x_one, ty, h_one)
+        torch.cuda.synchronize()
+        assert torch.equal(x_one, x_two) and torch.equal(h_one, h_two), "fused pass differs from the two kernels"
+        assert np.array_equal(x_one.cpu().numpy(), x + y)
+        _bf16_close(host(h_one), ob.rmsnorm((x + y).astype(np.float64)), "residual add + rmsnorm %dx%d" % (rows, d))
+
+
+def test_block_stack_with_deferred_updates_equals_block_by_block():
+    """A stack whose feed-forward updates are handed on to the next block's first kernel gives the
+    residual stream of the stack run block by block, bit for bit."""
+    w = fi.workload("cfg5_sparse_sync")
+    seg = np.array([0, 100, 228, 420], dtype=np.int32)
+    d_model, hidden, T, n_blocks = 512, 704, 420, 3
+    p = fa.make_params(3, w.n_q_heads, w.n_kv_heads, w.head_dim, 2, BF16)
+    buf = BlockBuffers(p, T, d_model, hidden)
+    x0 = torch.from_numpy(fi.hidden_input(w, d_model, total=T).astype(np.float32)).cuda()
+    wts = [BlockWeights(*(dev(fi.block_weights(w, b, d_model, hidden)[k], BF16) for k in ("qkv", "o", "gate_up", "down")))
+           for b in range(n_blocks)]
+    xa = x0.clone()
+    for b in range(n_blocks):
+        block_forward(p, b, xa, wts[b], seg, buf)
+    xb, pending = x0.clone(), None
+    say("block stack, updates deferred into the next normalisation")
+    for b in range(n_blocks):
+        pending = block_forward(p, b, xb, wts[b], seg, buf, pending=pending, defer_update=True)["pending"]
+    fa.fedattn_residual_add(xb, pending)
+    torch.cuda.synchronize()
+    assert torch.equal(xa, xb)
+
+
 def test_block_op_errors_are_return_codes():
     x = torch.zeros(4, 6, device="cuda")
     with pytest.raises(fa.FedAttnError) as e:
