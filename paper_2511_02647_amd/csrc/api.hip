@@ -343,14 +343,11 @@ fedattn_status fedattn_prefill_blocks(const fedattn_params* params, int32_t bloc
                      nullptr, 0, -1, nullptr, 0, stream);
 }
 
-// fused: blocks of one kind (local / sync) share launches, as many per launch as the workspace
-// has slices for; otherwise one launch (pair) per block in block order
-static fedattn_status run_decode(bool fused, const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
-                                 const void* q, const void* k_cache, const void* v_cache, void* out,
-                                 int64_t q_block_stride, int64_t cache_block_stride,
-                                 const int32_t* seg_offsets, const int32_t* seg_lens,
-                                 const int32_t* remote_lens, int32_t sync_override, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
+// Everything about a decode call that can be checked without the workspace or the device.
+static fedattn_status check_decode_args(const fedattn_params* params, int32_t block_idx0, int32_t n_blocks, const void* q,
+                                        const void* k_cache, const void* v_cache, void* out, int64_t q_block_stride,
+                                        int64_t cache_block_stride, const int32_t* seg_offsets, const int32_t* seg_lens,
+                                        const int32_t* remote_lens, int32_t sync_override) {
   fedattn_status st = check_params(params);
   if (st != FEDATTN_OK) return st;
   st = check_offsets(params, seg_offsets);
@@ -375,6 +372,24 @@ static fedattn_status run_decode(bool fused, const fedattn_params* params, int32
   if (n_blocks > 1 && (q_block_stride % 8 != 0 || cache_block_stride % 8 != 0 || q_block_stride < 0 ||
                        cache_block_stride < 0))
     return fail(FEDATTN_EINVAL, "block strides must be non-negative multiples of 8 elements");
+
+  return FEDATTN_OK;
+}
+
+// fused: blocks of one kind (local / sync) share launches, as many per launch as the workspace
+// has slices for; otherwise one launch (pair) per block in block order
+static fedattn_status run_decode(bool fused, const fedattn_params* params, int32_t block_idx0, int32_t n_blocks,
+                                 const void* q, const void* k_cache, const void* v_cache, void* out,
+                                 int64_t q_block_stride, int64_t cache_block_stride,
+                                 const int32_t* seg_offsets, const int32_t* seg_lens,
+                                 const int32_t* remote_lens, int32_t sync_override, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  fedattn_status st = check_decode_args(params, block_idx0, n_blocks, q, k_cache, v_cache, out, q_block_stride,
+                                        cache_block_stride, seg_offsets, seg_lens, remote_lens, sync_override);
+  if (st != FEDATTN_OK) return st;
+  if (n_blocks == 0) return FEDATTN_OK;
+  const int N = params->n_participants;
+  const int32_t capacity = seg_offsets[N];
 
   const bool mfma = params->dtype == FEDATTN_BF16 && (params->head_dim == 64 || params->head_dim == 128);
   const size_t esize = params->dtype == FEDATTN_BF16 ? 2 : 4;
@@ -566,9 +581,8 @@ fedattn_status fedattn_decode_static(const fedattn_params* params, int32_t block
                                      const void* k_cache, const void* v_cache, void* out,
                                      const int32_t* seg_offsets, const int32_t* seg_lens,
                                      const int32_t* remote_lens, int32_t sync_override, void* stream) {
-  fedattn_status st = check_params(params);
-  if (st != FEDATTN_OK) return st;
-  st = check_offsets(params, seg_offsets);
+  fedattn_status st = check_decode_args(params, block_idx, 1, q, k_cache, v_cache, out, 0, 0, seg_offsets, seg_lens,
+                                        remote_lens, sync_override);
   if (st != FEDATTN_OK) return st;
   const size_t need = decode_ws_bytes(params, seg_offsets[params->n_participants]);
   if (need > (size_t)FEDATTN_STATIC_SCRATCH_BYTES)
