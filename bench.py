@@ -55,10 +55,11 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 #   mfma_util      SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES): share of the cycles a
 #                  busy CU's matrix pipes were busy
 PMC = {
-    "cfg3_H4": {"source": None, "traffic_bytes": None, "mfma_util": None},
-    "cfg5": {"source": None, "traffic_bytes": None, "mfma_util": None},
-    "cfg2": {"source": None, "traffic_bytes": None, "mfma_util": None},
-    "decode": {"source": None, "traffic_bytes": None},
+    "cfg3": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 544289849, "mfma_util": 0.574},
+    "cfg3_H4": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 493950032, "mfma_util": 0.565},
+    "cfg5": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 1053378878, "mfma_util": 0.530},
+    "cfg2": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 42180065, "mfma_util": 0.293},
+    "decode": {"source": "profiles/hbm_traffic_pmc.txt", "traffic_bytes": 82282004},
 }
 
 CFG3_SWEEP = (1, 4, 8, 32)
@@ -325,10 +326,12 @@ class DecodeBench:
         return [capture(lambda s=s: self.run_step(s, sync_override, fused), self.out) for s in steps]
 
 
-def decode_leg(iterations: int) -> dict:
+def decode_leg(iterations: int, n_steps: int | None = None) -> dict:
     db = DecodeBench()
     w = db.w
     all_steps = list(range(w.decode_steps))
+    if n_steps is not None and n_steps < w.decode_steps:   # profiler runs: evenly spread steps of the run
+        all_steps = sorted(set(int(s) for s in np.linspace(0, w.decode_steps - 1, n_steps)))
     t0 = time.time()
     graphs = db.graphs(all_steps)
     log("decode: %d step graphs captured and checked in %.1f s" % (len(graphs), time.time() - t0))
@@ -458,11 +461,14 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--legs", default="cfg3,cfg5,cfg2,decode",
-                    help="comma-separated: cfg3 (the H sweep), cfg3_H1|H4|H8|H32 (one H), cfg5, cfg2, decode")
+                    help="comma-separated: cfg3 (the H sweep), cfg3_H1|H4|H8|H32 (one H), cfg5, cfg2, decode; copy (a plain "
+                         "copy of known size, the yardstick of the HBM-traffic counters)")
     ap.add_argument("--end-to-end", action="store_true",
                     help="also run the 8-block mini-Transformer of the end-to-end configuration (adds ~20 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-iterations", type=int, default=20, help="timed passes over the 256 decoding steps")
+    ap.add_argument("--decode-steps", type=int, default=None,
+                    help="time this many evenly spread decoding steps instead of all 256 (for profiler runs)")
     ap.add_argument("--data-blocks", type=int, default=None, help="distinct input blocks kept resident (large workloads)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -498,7 +504,7 @@ def main() -> int:
             legs["cfg3_H%d" % H] = prefill_leg(pb, H, ms[:, i], "cfg3_H%d" % H, max(3, args.steps // 4))
             log("  cfg3 H=%d: %.2f ms, %.1f TFLOP/s (%.1f%% of peak)" % (H, legs["cfg3_H%d" % H]["ms_per_step"],
                 legs["cfg3_H%d" % H]["value"], 100 * legs["cfg3_H%d" % H]["frac_of_bf16_peak"]))
-        pmc = PMC.get("cfg3_H4", {})
+        pmc = PMC.get("cfg3" if cfg3_hs == list(CFG3_SWEEP) else "cfg3_H%d" % cfg3_hs[0], {})
         achieved = fl_sweep / (ev_ms * 1e-3) / 1e12
         headline = {
             "value": tflops, "ms_per_step": wall * 1e3,
@@ -551,9 +557,30 @@ def main() -> int:
         del g, pb
         torch.cuda.empty_cache()
 
+    if "copy" in legs_req:
+        # a plain copy of known size (fedattn_aggregate_kv from separate allocations), the yardstick the
+        # FETCH_SIZE / WRITE_SIZE counters of the other legs are scaled by; not part of a default run
+        w = fi.workload("cfg3_hetero_prefill")
+        p3 = fa.make_params(w.n_participants, w.n_q_heads, w.n_kv_heads, w.head_dim, 4, torch.bfloat16)
+        seg = w.seg_offsets
+        kl = [torch.randn(int(seg[i + 1] - seg[i]), w.n_kv_heads, w.head_dim, device="cuda").to(torch.bfloat16)
+              for i in range(w.n_participants)]
+        vl = [t.clone() for t in kl]
+        kg = torch.empty(w.total_tokens, w.n_kv_heads, w.head_dim, dtype=torch.bfloat16, device="cuda")
+        vg = torch.empty_like(kg)
+        run = lambda: fa.fedattn_aggregate_kv(p3, kl, vl, seg, kg, vg)
+        _, ms = timed_replays([run], args.steps, args.warmup)
+        nbytes = 2 * kg.numel() * 2
+        legs["copy"] = {"kernel": "aggregate_kv_kernel", "bytes_read": nbytes, "bytes_written": nbytes,
+                        "us": float(np.median(ms)) * 1e3, "GBps": 2 * nbytes / (float(np.median(ms)) * 1e-3) / 1e9}
+        log("copy: %d bytes in, %d bytes out, %.1f us" % (nbytes, nbytes, legs["copy"]["us"]))
+        if headline is None:
+            headline = {"value": legs["copy"]["GBps"], "ms_per_step": legs["copy"]["us"] * 1e-3, "unit": "GB/s",
+                        "config": {"workload": "copy calibration"}, "roofline": None}
+
     decode = None
     if "decode" in legs_req:
-        decode = decode_leg(args.decode_iterations)
+        decode = decode_leg(args.decode_iterations, args.decode_steps)
         log("decode: %.0f GB/s over %d steps x %d blocks (%.1f%% of HBM peak; local block-steps %.0f, sync %.0f, "
             "blocks sharing launches %.0f GB/s)" % (decode["value"], decode["steps_timed"], decode["blocks"],
             100 * decode["frac_of_hbm_peak"], decode["roofline"]["local_GBps"], decode["roofline"]["sync_GBps"],
