@@ -18,6 +18,8 @@ Legs (each with its own `roofline` object):
   cfg2        Llama-3-8B shape, 4 x 512 tokens (the smallest bf16 workload; launch-dominated).
   decode      cfg4: 16 participants, 256 decoding steps x 32 blocks, every step replayed from
               its own graph (the cache lengths grow step by step), GB/s over the whole run.
+  peaks       what this machine reaches on the bare resources (a streaming read of a block-step's size,
+              an MFMA-only loop), so that every roofline also carries a fraction of a measured peak.
 
 Prints ONE JSON line.  `value` is useful attention TFLOP/s of the headline workload
 (4*D*Hq*visible pairs; masked pairs and softmax not counted).  `roofline` is for the
@@ -375,6 +377,39 @@ def decode_leg(iterations: int, n_steps: int | None = None) -> dict:
                          "kinds_measured_on_steps": sample}}
 
 
+def measured_peaks() -> dict:
+    """What this machine reaches on the bare resources, measured with the library's probe kernels in the
+    same run: a streaming read of one decode block-step's size per launch (32 launches over
+    distinct buffers per graph replay, like the blocks of a decoding step), contiguous and in
+    the decode cache's layout, and an MFMA-only loop."""
+    n_launch, per = 32, 75_530_240          # the mean block-step of the decode workload
+    stride = (per + (1 << 20) - 1) >> 20 << 20
+    buf = torch.zeros(n_launch * stride, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1 << 18, dtype=torch.float32, device="cuda")
+    out = {}
+    for pattern, name in ((0, "stream_contiguous"), (1, "stream_cache_layout")):
+        moved = []
+
+        def run():
+            moved.clear()
+            for b in range(n_launch):
+                moved.append(fa.fedattn_probe_stream(buf[b * stride:b * stride + per], pattern, sink))
+        g = capture(run, sink)
+        _, ms = timed_replays([g.replay], 20, 2)
+        us = float(np.median(ms)) * 1e3 / n_launch
+        out[name] = {"GBps": moved[0] / us / 1e3, "bytes_per_launch": moved[0], "us_per_launch": us,
+                     "frac_of_published_peak": moved[0] / us / 1e3 / PEAK_HBM_GBS}
+        del g
+    flops = []
+    run = lambda: flops.append(fa.fedattn_probe_mfma(sink, 20000))
+    _, ms = timed_replays([run], 5, 1)
+    out["mfma_bf16_loop"] = {"TFLOPs": flops[-1] / (float(np.median(ms)) * 1e-3) / 1e12,
+                             "frac_of_published_peak": flops[-1] / (float(np.median(ms)) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    out["how"] = ("fedattn_probe_stream: %d launches of %.1f MB over distinct buffers per graph replay, median of 20 replays; "
+                  "fedattn_probe_mfma: v_mfma_f32_32x32x16_bf16 on register operands, two wavefronts per SIMD" % (n_launch, per / 1e6))
+    return out
+
+
 def end_to_end_leg(steps: int) -> dict:
     """The end-to-end configuration: the 8-block mini-Transformer (d_model 2048, feed-forward 5632,
     16/4 heads of 128) through the FedAttn schedule on 16 x 4096 tokens, sparse exchange in the
@@ -460,8 +495,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--legs", default="cfg3,cfg5,cfg2,decode",
-                    help="comma-separated: cfg3 (the H sweep), cfg3_H1|H4|H8|H32 (one H), cfg5, cfg2, decode; copy (a plain "
+    ap.add_argument("--legs", default="cfg3,cfg5,cfg2,decode,peaks",
+                    help="comma-separated: cfg3 (the H sweep), cfg3_H1|H4|H8|H32 (one H), cfg5, cfg2, decode, peaks (streaming-read and "
+                         "MFMA-only rates of this box); copy (a plain "
                          "copy of known size, the yardstick of the HBM-traffic counters)")
     ap.add_argument("--end-to-end", action="store_true",
                     help="also run the 8-block mini-Transformer of the end-to-end configuration (adds ~20 s)")
@@ -587,6 +623,22 @@ def main() -> int:
             decode["roofline"]["blocks_fused_GBps"]))
         torch.cuda.empty_cache()
 
+    peaks = None
+    if "peaks" in legs_req:
+        peaks = measured_peaks()
+        log("measured on this box: streaming read %.0f GB/s contiguous, %.0f GB/s in the decode cache's layout (%.1f MB per "
+            "launch); MFMA-only loop %.0f TFLOP/s" % (peaks["stream_contiguous"]["GBps"], peaks["stream_cache_layout"]["GBps"],
+                                                       peaks["stream_contiguous"]["bytes_per_launch"] / 1e6,
+                                                       peaks["mfma_bf16_loop"]["TFLOPs"]))
+        if decode is not None:
+            decode["roofline"]["frac_of_measured_stream_in_cache_layout"] = decode["value"] / peaks["stream_cache_layout"]["GBps"]
+        for leg in legs.values():
+            if isinstance(leg, dict) and leg.get("roofline") and leg["roofline"].get("bound") == "mfma":
+                leg["roofline"]["frac_of_measured_mfma_loop"] = leg["value"] / peaks["mfma_bf16_loop"]["TFLOPs"]
+        if headline is not None and headline.get("roofline") and headline["roofline"].get("bound") == "mfma":
+            headline["roofline"]["frac_of_measured_mfma_loop"] = headline["value"] / peaks["mfma_bf16_loop"]["TFLOPs"]
+        torch.cuda.empty_cache()
+
     if headline is None and decode is not None:
         headline = {"value": decode["value"], "ms_per_step": decode["ms_per_run"], "config": {"workload": decode["workload"]},
                     "roofline": decode["roofline"], "unit": "GB/s"}
@@ -602,6 +654,8 @@ def main() -> int:
               "roofline": headline["roofline"], "legs": legs}
     if decode is not None:
         result["decode"] = decode
+    if peaks is not None:
+        result["measured_peaks"] = peaks
     if cost is not None:
         result["analytic_cost_per_participant"] = cost
     if cpu is not None:

@@ -279,6 +279,22 @@ FEDATTN_API fedattn_status fedattn_residual_add(float* x, const void* y, int64_t
 FEDATTN_API fedattn_status fedattn_residual_add_rmsnorm(float* x, const void* y, void* out, int64_t rows, int32_t d_model,
                                             float eps, void* stream);
 
+/*
+ * Measurement aids (no part of the method): the rates the GPU reaches on the bare resources the
+ * attention kernels are bound by, for benchmarks that report a fraction of a measured peak beside
+ * the fraction of the published one.  Each call enqueues ONE kernel; the caller times it.
+ * fedattn_probe_stream: one workgroup per CU reads `bytes` bytes at src (device, 16-byte aligned;
+ *   rounded down to whole tiles per workgroup) through LDS rings with the direct HBM -> LDS loads of
+ *   the decode kernel and does nothing else.  pattern 0: contiguous shares.  pattern 1: the decode
+ *   kernel's access pattern on a [rows, 8 KV heads, 128] bf16 cache (256-byte pieces at a 2 KB
+ *   stride, from a K array in the first half of the buffer and a V array in the second).  sink:
+ *   device, one float per workgroup (never written in practice).  Returns the bytes read, -1 on error.
+ * fedattn_probe_mfma: every SIMD runs two wavefronts that issue `iters` x 8 v_mfma_f32_32x32x16_bf16
+ *   on register operands.  sink: device, 512 floats per CU.  Returns the FLOPs performed, -1 on error.
+ */
+FEDATTN_API int64_t fedattn_probe_stream(const void* src, int64_t bytes, int32_t pattern, void* sink, void* stream);
+FEDATTN_API int64_t fedattn_probe_mfma(void* sink, int32_t iters, void* stream);
+
 /* Reason of the calling thread's most recent failure ("" if none). */
 FEDATTN_API const char* fedattn_last_error(void);
 

@@ -27,7 +27,7 @@ EXPORTS = ("fedattn_is_sync_block", "fedattn_workspace_bytes", "fedattn_prefill"
            "fedattn_prefill_blocks", "fedattn_decode", "fedattn_decode_blocks", "fedattn_decode_blocks_fused",
            "fedattn_decode_static", "fedattn_aggregate_kv",
            "fedattn_rmsnorm", "fedattn_rope_split_qkv", "fedattn_swiglu", "fedattn_residual_add",
-           "fedattn_residual_add_rmsnorm",
+           "fedattn_residual_add_rmsnorm", "fedattn_probe_stream", "fedattn_probe_mfma",
            "fedattn_last_error", "fedattn_version")
 
 
@@ -89,6 +89,10 @@ def load():
     lib.fedattn_residual_add.restype = ctypes.c_int
     lib.fedattn_residual_add_rmsnorm.argtypes = [vp, vp, vp, i64, i32, fl, vp]
     lib.fedattn_residual_add_rmsnorm.restype = ctypes.c_int
+    lib.fedattn_probe_stream.argtypes = [vp, i64, i32, vp, vp]
+    lib.fedattn_probe_stream.restype = i64
+    lib.fedattn_probe_mfma.argtypes = [vp, i32, vp]
+    lib.fedattn_probe_mfma.restype = i64
     lib.fedattn_last_error.restype = ctypes.c_char_p
     lib.fedattn_version.restype = ctypes.c_char_p
     _lib = lib
@@ -331,3 +335,20 @@ def fedattn_residual_add_rmsnorm(x: torch.Tensor, y: torch.Tensor, out: torch.Te
         raise TypeError("residual_add_rmsnorm: x fp32, y and out bf16, all [rows, d_model]")
     _check(load().fedattn_residual_add_rmsnorm(_dev(x, "x"), _dev(y, "y"), _dev(out, "out"), x.shape[0], x.shape[1],
                                                float(eps), _stream(stream)))
+
+
+def fedattn_probe_stream(src: torch.Tensor, pattern: int, sink: torch.Tensor, stream=None) -> int:
+    """One streaming-read kernel over `src` (pattern 0 contiguous, 1 the decode cache layout); returns the bytes read."""
+    n = load().fedattn_probe_stream(_dev(src, "src"), src.numel() * src.element_size(), int(pattern), _dev(sink, "sink"),
+                                    _stream(stream))
+    if n < 0:
+        raise FedAttnError(FEDATTN_EINVAL, load().fedattn_last_error().decode())
+    return int(n)
+
+
+def fedattn_probe_mfma(sink: torch.Tensor, iters: int, stream=None) -> int:
+    """One MFMA-only kernel; returns the FLOPs it performs."""
+    n = load().fedattn_probe_mfma(_dev(sink, "sink"), int(iters), _stream(stream))
+    if n < 0:
+        raise FedAttnError(FEDATTN_EINVAL, load().fedattn_last_error().decode())
+    return int(n)

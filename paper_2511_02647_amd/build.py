@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfedattn.so")
-SOURCES = ["api.hip", "prefill_generic.hip", "prefill_mfma.hip", "decode.hip", "aggregate.hip", "block_ops.hip"]
+SOURCES = ["api.hip", "prefill_generic.hip", "prefill_mfma.hip", "decode.hip", "aggregate.hip", "block_ops.hip", "probes.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-fvisibility=hidden", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -696,6 +696,41 @@ fedattn_status fedattn_residual_add(float* x, const void* y, int64_t n, void* st
   return FEDATTN_OK;
 }
 
+// ---- measurement aids ---------------------------------------------------------------------
+int64_t fedattn_probe_stream(const void* src, int64_t bytes, int32_t pattern, void* sink, void* stream) {
+  if (!src || !sink || !aligned16(src) || bytes <= 0 || (pattern != 0 && pattern != 1)) {
+    fail(FEDATTN_EINVAL, "probe_stream: src and sink non-NULL, src 16-byte aligned, bytes > 0, pattern 0 or 1");
+    return -1;
+  }
+  const int n_wgs = device_cus() / 8 * 8;
+  const int64_t unit = pattern == 0 ? (int64_t)n_wgs * 32768 : (int64_t)n_wgs * 64 * 256 * 2;
+  const int64_t moved = bytes / unit * unit;
+  if (moved == 0) {
+    fail(FEDATTN_EINVAL, "probe_stream: at least %lld bytes", (long long)unit);
+    return -1;
+  }
+  hipError_t e = launch_stream_probe(src, moved, n_wgs, pattern, reinterpret_cast<float*>(sink), reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    fail(FEDATTN_ELAUNCH, "probe_stream: %s", hipGetErrorString(e));
+    return -1;
+  }
+  return moved;
+}
+
+int64_t fedattn_probe_mfma(void* sink, int32_t iters, void* stream) {
+  if (!sink || iters <= 0) {
+    fail(FEDATTN_EINVAL, "probe_mfma: sink non-NULL, iters > 0");
+    return -1;
+  }
+  const int n_wgs = device_cus();
+  hipError_t e = launch_mfma_probe(reinterpret_cast<float*>(sink), n_wgs, iters, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    fail(FEDATTN_ELAUNCH, "probe_mfma: %s", hipGetErrorString(e));
+    return -1;
+  }
+  return (int64_t)n_wgs * 8 /* wavefronts */ * iters * 8 /* MFMAs */ * (2LL * 32 * 32 * 16);
+}
+
 const char* fedattn_last_error(void) { return g_err; }
 
 const char* fedattn_version(void) { return "fedattn-gfx950 0.1"; }

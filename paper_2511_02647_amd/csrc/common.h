@@ -118,6 +118,8 @@ hipError_t launch_rope_split(const void* qkv, const int32_t* pos, void* q, void*
                              int Hkv, int D, float theta, hipStream_t s);
 hipError_t launch_swiglu(const void* gate_up, void* out, int64_t rows, int F, hipStream_t s);
 hipError_t launch_residual_add(float* x, const void* y, int64_t n, hipStream_t s);
+hipError_t launch_stream_probe(const void* src, int64_t bytes, int n_wgs, int pattern, float* sink, hipStream_t s);
+hipError_t launch_mfma_probe(float* sink, int n_wgs, int iters, hipStream_t s);
 
 // A kernel's dynamic-LDS limit is a per-device attribute: set it the first time the kernel is
 // launched on a device (`done` holds one bit per device; setting it twice is harmless).
