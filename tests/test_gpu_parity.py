@@ -555,6 +555,55 @@ def test_decode_local_chunk_merge_in_kernel_with_dirty_workspace():
         check(host(out), ref, BF16, "decode local in-kernel merge, call %d" % rep)
 
 
+@pytest.mark.parametrize("N,Hkv,G,cap,n_lens", [(16, 8, 4, 1280, 1152), (2, 2, 4, 4096, 4000)])
+def test_decode_local_merge_is_reproducible_over_alternating_inputs(N, Hkv, G, cap, n_lens):
+    """The in-kernel merge hands partials from workgroup to workgroup through the workspace.  Launch
+    after launch over the same workspace, alternating between two sets of queries and caches: every
+    result must equal, bit for bit, the first result of its input (the merge sums the chunks in a
+    fixed order, so the result does not depend on which workgroup arrives last; a partial read
+    stale would be the other input's).  Shapes: the decode workload's (2 chunks per segment) and
+    two long segments (64 chunks per segment); single launches and blocks sharing a launch in
+    their own workspace slices.  Stops at the first mismatch."""
+    Hq, D, M = Hkv * G, 128, 6
+    seg = (np.arange(N + 1) * cap).astype(np.int32)
+    lens = np.full(N, n_lens, dtype=np.int32)
+    lens[-1] = n_lens - 37
+    p = fa.make_params(N, Hq, Hkv, D, 0, BF16)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(91)
+    sets = []
+    for i in range(2):
+        sets.append((torch.randn(M, N, Hq, D, generator=g, device="cuda", dtype=BF16),
+                     torch.randn(M, N * cap, Hkv, D, generator=g, device="cuda", dtype=BF16),
+                     torch.randn(M, N * cap, Hkv, D, generator=g, device="cuda", dtype=BF16)))
+    one = fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_DECODE, N * cap)
+    slice_bytes = (one + 255) // 256 * 256
+    ws = torch.full((one + (M - 1) * slice_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    # the oracle on one block of the first input, so that "the first result" is a checked one
+    q0, k0, v0 = (host(t[0]) for t in sets[0])
+    first = [None, None]
+    first_fused = [None, None]
+    for it in range(200):
+        i = it & 1
+        tq, tk, tv = sets[i]
+        out = torch.full_like(tq[0], float("nan"))
+        fa.fedattn_decode(p, 0, tq[0], tk[0], tv[0], out, seg, lens, sync_override=0, workspace=ws)
+        fused = torch.full_like(tq, float("nan"))
+        fa.fedattn_decode_blocks_fused(p, 0, M, tq, tk, tv, fused, tq[0].numel(), tk[0].numel(), seg, lens,
+                                       sync_override=0, workspace=ws)
+        torch.cuda.synchronize()
+        if first[i] is None:
+            say("decode local, alternating inputs, N=%d chunks over %d rows: first results" % (N, n_lens))
+            first[i], first_fused[i] = out, fused
+            assert torch.equal(fused[0], out), "blocks sharing a launch differ from the single launch"
+            if i == 0:
+                check(host(out), oracle.decode_step(q0, k0, v0, seg, lens, is_sync=False), BF16,
+                      "decode local, N=%d, %d rows" % (N, n_lens))
+            continue
+        assert torch.equal(out, first[i]), "launch %d (input %d) differs from the first result of its input" % (it, i)
+        assert torch.equal(fused, first_fused[i]), "fused launch %d (input %d) differs from its first result" % (it, i)
+
+
 def test_decode_blocks_equals_per_block_calls():
     N, Hq, Hkv, D, cap, M, H = 4, 8, 2, 128, 200, 4, 2
     seg = (np.arange(N + 1) * cap).astype(np.int32)
