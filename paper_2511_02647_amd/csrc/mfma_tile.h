@@ -27,7 +27,6 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units a row maximum may lag be
 // scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier
 #define FEDATTN_SGB_MFMA 0x008
 #define FEDATTN_SGB_DS_READ 0x100
-#define FEDATTN_SGB_VALU 0x402  // vector ALU incl. transcendentals, MFMA excluded
 
 // One direct-to-LDS load: every lane fetches 16 bytes from base + off (bytes) and the
 // wavefront's 1 KB lands at LDS byte address lds_addr (+16 per lane).  base and
@@ -168,10 +167,7 @@ struct KvTile {
   }
 
   // S^T[kv][q] = K Q^T from the K stage at LDS byte offset kb.  LDS reads run 3 k-steps
-  // ahead of the MFMAs that consume them.  VALU_PER_STEP > 0 asks the scheduler to place
-  // that many independent vector-ALU instructions of the surrounding code (the softmax
-  // of the previous tile) after each k-step's pair of MFMAs.
-  template <int VALU_PER_STEP = 0>
+  // ahead of the MFMAs that consume them.
   __device__ __attribute__((always_inline)) void scores(lds_cptr lds0, int kb, const bf16x8 (&qf)[KSTEPS],
                                                         f32x16 (&s)[2]) const {
 #pragma unroll
@@ -195,12 +191,10 @@ struct KvTile {
     for (int st = 0; st < KSTEPS - kLook; ++st) {
       __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_MFMA, 2, 0);
       __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_DS_READ, 2, 0);
-      if constexpr (VALU_PER_STEP > 0) __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_VALU, VALU_PER_STEP, 0);
     }
 #pragma unroll
     for (int st = 0; st < kLook; ++st) {
       __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_MFMA, 2, 0);
-      if constexpr (VALU_PER_STEP > 0) __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_VALU, VALU_PER_STEP, 0);
     }
   }
 

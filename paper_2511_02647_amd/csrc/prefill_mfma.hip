@@ -32,8 +32,9 @@ namespace fedattn {
 namespace {
 
 // NG = 1: 4 wavefronts per workgroup (two workgroups share a CU when the grid is large
-// enough, and one's matrix work overlaps the other's softmax: a single wavefront cannot
-// overlap its own vector ALU work with its own MFMAs).  NG = 2, for grids that would
+// enough, and one's matrix work overlaps the other's softmax: inside a wavefront the softmax
+// sits between the two products that depend on it, and spreading it under the MFMAs of the
+// neighbouring tiles instead measured slower).  NG = 2, for grids that would
 // leave one workgroup per CU: 8 wavefronts = two groups of 4 on the same query rows;
 // group g takes the KV tiles j with j mod 2 == g through its own LDS stages and the two
 // partial results are merged at the end (split-KV inside the workgroup).

@@ -732,8 +732,21 @@ def test_prefill_sync_local_kv_in_place_and_through_a_copy(dtype):
     kt = oracle.expand_keep_chunks(flags, seg, 16)
     views_k = [tk[seg[n]:seg[n + 1]] for n in range(N)]
     views_v = [tv[seg[n]:seg[n + 1]] for n in range(N)]
-    apart_k = [x.clone() if x.numel() else None for x in views_k]      # separate allocations
-    apart_v = [x.clone() if x.numel() else None for x in views_v]
+
+    def apart(views):
+        """The participants' matrices in reverse order, one row of padding between them, inside one
+        allocation: never back to back in participant order, whatever the allocator does."""
+        pool = torch.zeros(420 + N, Hkv, D, dtype=dtype, device="cuda")
+        out, at = [None] * N, 0
+        for n in reversed(range(N)):
+            rows = views[n].shape[0]
+            if rows:
+                pool[at:at + rows].copy_(views[n])
+                out[n] = pool[at:at + rows]
+            at += rows + 1
+        return out
+
+    apart_k, apart_v = apart(views_k), apart(views_v)
     ws_pre = torch.empty(max(16, fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_PREFILL, 420, 16)), dtype=torch.uint8, device="cuda")
     ws_all = torch.empty(fa.fedattn_workspace_bytes(p, fa.FEDATTN_OP_PREFILL_SYNC_LOCAL_KV, 420, 16), dtype=torch.uint8, device="cuda")
     for sparse in (False, True):
