@@ -259,7 +259,7 @@ def prefill_leg(pb: PrefillBench, H: int, ms_step: np.ndarray, pmc_key: str | No
     pmc = PMC.get(pmc_key or "", {})
     roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
             "traffic": pmc.get("traffic_bytes"), "mfma_util": pmc.get("mfma_util"), "counters_from": pmc.get("source"),
-            "kernel": "prefill_mfma_kernel<128, *>", "launches_per_step": pb.M,
+            "kernel": "prefill_mfma_kernel<128, *, true>", "launches_per_step": pb.M,
             "flop_per_launch": fl_step / pb.M, "avg_launch_us": med * 1e3 / pb.M,
             "timing": "HIP events around the graph replay of the step's %d launches on the replay stream, median of %d "
                       "replays, divided by the launches (gaps between graph nodes included: the figure errs low)"
@@ -556,7 +556,7 @@ def main() -> int:
             "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                          "frac": achieved / PEAK_BF16_TFLOPS, "traffic": pmc.get("traffic_bytes"),
                          "mfma_util": pmc.get("mfma_util"), "counters_from": pmc.get("source"),
-                         "kernel": "prefill_mfma_kernel<128, 1>", "launches_per_step": n_launch,
+                         "kernel": "prefill_mfma_kernel<128, 1, true>", "launches_per_step": n_launch,
                          "flop_per_launch": fl_sweep / n_launch, "avg_launch_us": ev_ms * 1e3 / n_launch,
                          "timing": "HIP events around every graph replay of the timed steps on the replay stream, median over "
                                    "%d steps of the step's total, divided by its %d launches" % (args.steps, n_launch)}}

@@ -28,6 +28,7 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units a row maximum may lag be
 #define FEDATTN_SGB_MFMA 0x008
 #define FEDATTN_SGB_DS_READ 0x100
 
+
 // One direct-to-LDS load: every lane fetches 16 bytes from base + off (bytes) and the
 // wavefront's 1 KB lands at LDS byte address lds_addr (+16 per lane).  base and
 // lds_addr must be wave-uniform.  The instruction is written out so that the compiler
@@ -166,12 +167,14 @@ struct KvTile {
     }
   }
 
-  // S^T[kv][q] = K Q^T from the K stage at LDS byte offset kb.  LDS reads run 3 k-steps
-  // ahead of the MFMAs that consume them.
+  // S^T[kv][q] = K Q^T from the K stage at LDS byte offset kb.  LDS reads run 2 k-steps
+  // ahead of the MFMAs that consume them (1 to 4 measure the same; 2 leaves the registers for `init`).
+  // `init` is what the accumulation starts from: zeros, or minus the reference value of the
+  // softmax in every element (the scores then come out relative to it at no cost).
   __device__ __attribute__((always_inline)) void scores(lds_cptr lds0, int kb, const bf16x8 (&qf)[KSTEPS],
-                                                        f32x16 (&s)[2]) const {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) { s[0][e] = 0.f; s[1][e] = 0.f; }
+                                                        const f32x16& init, f32x16 (&s)[2]) const {
+    s[0] = init;
+    s[1] = init;
     bf16x8 kf[KSTEPS][2];
 #pragma unroll
     for (int st = 0; st < KSTEPS; ++st) {
@@ -185,7 +188,7 @@ struct KvTile {
     for (int st = 0; st < KSTEPS; ++st)
 #pragma unroll
       for (int aa = 0; aa < 2; ++aa) s[aa] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st][aa], qf[st], s[aa], 0, 0, 0);
-    constexpr int kLook = KSTEPS > 3 ? 3 : KSTEPS - 1;
+    constexpr int kLook = KSTEPS > 2 ? 2 : KSTEPS - 1;
     __builtin_amdgcn_sched_group_barrier(FEDATTN_SGB_DS_READ, 2 * kLook, 0);
 #pragma unroll
     for (int st = 0; st < KSTEPS - kLook; ++st) {
@@ -288,6 +291,60 @@ __device__ __attribute__((always_inline)) inline void softmax_exp(const f32x16 (
       const float p3 = __builtin_amdgcn_exp2f(fmaf(s[aa][e + 3], sc, -m_use));
       const bf16x2 q0 = {(bf16_t)p0, (bf16_t)p1};
       const bf16x2 q1 = {(bf16_t)p2, (bf16_t)p3};
+      ps0 = __builtin_amdgcn_fdot2_f32_bf16(q0, ones, ps0, false);
+      ps1 = __builtin_amdgcn_fdot2_f32_bf16(q1, ones, ps1, false);
+      pb[aa * 2 + (e >> 3)][e & 7] = q0[0];
+      pb[aa * 2 + (e >> 3)][(e & 7) + 1] = q0[1];
+      pb[aa * 2 + (e >> 3)][(e & 7) + 2] = q1[0];
+      pb[aa * 2 + (e >> 3)][(e & 7) + 3] = q1[1];
+    }
+  l_run += ps0 + ps1;
+}
+
+// The same step on scores that already are in the log2 domain and relative to the reference
+// value (the Q operand carries the scale, the score accumulation starts from -reference in
+// `neg_ref`): no multiply-subtract per score.  m_run is the reference in absolute terms
+// (-inf before the first tile), neg_ref holds -(m_run, or 0 while m_run is -inf) in every
+// element.  When a row's maximum has outgrown the reference by more than the threshold, the
+// reference moves there: accumulators and row sums are rescaled, the scores of this tile are
+// shifted, neg_ref is refilled.
+template <int DT>
+__device__ __attribute__((always_inline)) inline void softmax_step_rel(f32x16 (&s)[2], float& m_run, float& l_run,
+                                                                        f32x16 (&o)[DT], f32x16& neg_ref,
+                                                                        bf16x8 (&pb)[4]) {
+  float mx0 = fmaxf(s[0][0], s[1][0]);
+  float mx1 = fmaxf(s[0][1], s[1][1]);
+#pragma unroll
+  for (int e = 2; e < 16; e += 2) {
+    mx0 = fmaxf(fmaxf(mx0, s[0][e]), s[1][e]);
+    mx1 = fmaxf(fmaxf(mx1, s[0][e + 1]), s[1][e + 1]);
+  }
+  const float r = max_across_halves(fmaxf(mx0, mx1));  // row maximum relative to the reference
+  if (__builtin_amdgcn_ballot_w64(r > ((m_run == -INFINITY) ? -INFINITY : kRescaleThreshold)) != 0) {
+    const float ref_old = -neg_ref[0];
+    const float m_new = fmaxf(m_run, r + ref_old);
+    const float ref_new = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - ref_new);  // exp2(-inf) = 0 at the first tile
+    const float shift = ref_new - ref_old;
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      s[0][e] -= shift;
+      s[1][e] -= shift;
+      neg_ref[e] = -ref_new;
+    }
+  }
+  const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+  float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+  for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+    for (int e = 0; e < 16; e += 4) {
+      const bf16x2 q0 = {(bf16_t)__builtin_amdgcn_exp2f(s[aa][e]), (bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 1])};
+      const bf16x2 q1 = {(bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 2]), (bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 3])};
       ps0 = __builtin_amdgcn_fdot2_f32_bf16(q0, ones, ps0, false);
       ps1 = __builtin_amdgcn_fdot2_f32_bf16(q1, ones, ps1, false);
       pb[aa * 2 + (e >> 3)][e & 7] = q0[0];

@@ -130,6 +130,38 @@ def test_mfma_prefill_sync_rule_and_scale():
         check(got, glo if sync else loc, BF16, "rule H=%d block=%d -> %s" % (H, b, "sync" if sync else "local"))
 
 
+@pytest.mark.parametrize("D,scale", [(128, 0.0), (128, 0.3), (64, 0.0), (64, 0.4)])
+@pytest.mark.parametrize("trend", ["rising", "falling"])
+def test_mfma_prefill_scores_that_keep_outgrowing_the_reference(D, scale, trend):
+    """The online softmax keeps a reference value per row and moves it only when a tile's maximum
+    has outgrown it by 2^8: random inputs move it once, at the first tile.  Here the scores rise
+    over the first 320 keys by about 12 (in log2 units) per 64 keys, so that each of the first tiles
+    of a walk moves it (accumulators rescaled mid-walk), or fall at the same rate, so that it never
+    moves again and later weights underflow.  With the usual scale (0: 1/sqrt(D); the kernel folds it into Q) and
+    with a larger one (applied to the scores in fp32)."""
+    Hq, Hkv = 8, 2
+    seg = np.array([0, 300, 300, 937, 1200], dtype=np.int32)
+    total = int(seg[-1])
+    g = np.random.default_rng(40)
+    u = g.standard_normal(D)
+    u /= np.linalg.norm(u)
+    pos = np.arange(total, dtype=np.float64)
+    ramp = np.minimum(pos, 320.0) if trend == "rising" else np.maximum(320.0 - pos, 0.0)   # over the first five tiles
+    sc = scale if scale else D ** -0.5
+    per_key = 12.0 / 64.0 / (sc * np.log2(np.e))          # growth of q.k per key for 12 log2 units per tile
+    q = fi.round_to_bf16((u[None, None, :] * 4.0 + 0.3 * g.standard_normal((total, Hq, D))).astype(np.float32))
+    k = fi.round_to_bf16((u[None, None, :] * (ramp * per_key / 4.0)[:, None, None]
+                          + 0.3 * g.standard_normal((total, Hkv, D))).astype(np.float32))
+    v = fi.round_to_bf16(g.standard_normal((total, Hkv, D)).astype(np.float32))
+    for causal in (True, False):
+        for sync in (0, 1):
+            say("growing scores D=%d scale=%g %s causal=%d sync=%d" % (D, scale, trend, causal, sync))
+            got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, causal=causal,
+                          sync_override=sync, scale=scale)
+            ref = oracle.attend_block(q, k, v, seg, is_sync=bool(sync), causal=causal, scale=scale if scale else None)
+            check(got, ref, BF16, "growing scores D=%d scale=%g %s causal=%d sync=%d" % (D, scale, trend, causal, sync))
+
+
 @pytest.mark.parametrize("chunk", [64, 128])
 def test_mfma_prefill_sparse_exchange(chunk):
     seg = np.array([0, 256, 256, 579, 900, 1001], dtype=np.int32)   # ragged last chunks
