@@ -303,55 +303,71 @@ __device__ __attribute__((always_inline)) inline void softmax_exp(const f32x16 (
 
 // The same step on scores that already are in the log2 domain and relative to the reference
 // value (the Q operand carries the scale, the score accumulation starts from -reference in
-// `neg_ref`): no multiply-subtract per score.  m_run is the reference in absolute terms
-// (-inf before the first tile), neg_ref holds -(m_run, or 0 while m_run is -inf) in every
-// element.  When a row's maximum has outgrown the reference by more than the threshold, the
-// reference moves there: accumulators and row sums are rescaled, the scores of this tile are
-// shifted, neg_ref is refilled.
+// `neg_ref`): no multiply-subtract per score, and no row maxima either in the common case.
+// m_run is the reference in absolute terms (-inf before the first tile), neg_ref holds
+// -(m_run, or 0 while m_run is -inf) in every element.
+// The reference has to move only when a weight would exceed 2^threshold.  A lane's sum of
+// weights bounds each of them, and the sum is computed anyway: the exponentials are taken
+// first, against the reference as it stands, and only when some lane's sum of this tile
+// exceeds 2^threshold (or is not a number) are the row maxima computed, the reference moved
+// there, accumulators and row sums rescaled, the scores shifted, neg_ref refilled and the
+// exponentials taken again.  A first tile (no reference yet) starts with the maxima.  With a reference that lags the
+// running maximum by at most the threshold every weight stays <= 2^threshold, as before.
 template <int DT>
 __device__ __attribute__((always_inline)) inline void softmax_step_rel(f32x16 (&s)[2], float& m_run, float& l_run,
                                                                         f32x16 (&o)[DT], f32x16& neg_ref,
                                                                         bf16x8 (&pb)[4]) {
-  float mx0 = fmaxf(s[0][0], s[1][0]);
-  float mx1 = fmaxf(s[0][1], s[1][1]);
-#pragma unroll
-  for (int e = 2; e < 16; e += 2) {
-    mx0 = fmaxf(fmaxf(mx0, s[0][e]), s[1][e]);
-    mx1 = fmaxf(fmaxf(mx1, s[0][e + 1]), s[1][e + 1]);
-  }
-  const float r = max_across_halves(fmaxf(mx0, mx1));  // row maximum relative to the reference
-  if (__builtin_amdgcn_ballot_w64(r > ((m_run == -INFINITY) ? -INFINITY : kRescaleThreshold)) != 0) {
-    const float ref_old = -neg_ref[0];
-    const float m_new = fmaxf(m_run, r + ref_old);
-    const float ref_new = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - ref_new);  // exp2(-inf) = 0 at the first tile
-    const float shift = ref_new - ref_old;
-    m_run = m_new;
-    l_run *= alpha;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      s[0][e] -= shift;
-      s[1][e] -= shift;
-      neg_ref[e] = -ref_new;
-    }
-  }
   const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
-  float ps0 = 0.f, ps1 = 0.f;
+  const float limit = __builtin_amdgcn_exp2f(kRescaleThreshold);
+  float ps0, ps1;
+  bool moved = false;
+  bool move = __builtin_amdgcn_ballot_w64(m_run == -INFINITY) != 0;  // a first tile: straight to the maxima
+  while (true) {
+    if (move) {
+      float mx0 = fmaxf(s[0][0], s[1][0]);
+      float mx1 = fmaxf(s[0][1], s[1][1]);
 #pragma unroll
-  for (int aa = 0; aa < 2; ++aa)
+      for (int e = 2; e < 16; e += 2) {
+        mx0 = fmaxf(fmaxf(mx0, s[0][e]), s[1][e]);
+        mx1 = fmaxf(fmaxf(mx1, s[0][e + 1]), s[1][e + 1]);
+      }
+      const float r = max_across_halves(fmaxf(mx0, mx1));  // row maximum relative to the reference
+      const float ref_old = -neg_ref[0];
+      const float m_new = fmaxf(m_run, r + ref_old);
+      const float ref_new = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - ref_new);  // exp2(-inf) = 0 at the first tile
+      const float shift = ref_new - ref_old;
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
-    for (int e = 0; e < 16; e += 4) {
-      const bf16x2 q0 = {(bf16_t)__builtin_amdgcn_exp2f(s[aa][e]), (bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 1])};
-      const bf16x2 q1 = {(bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 2]), (bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 3])};
-      ps0 = __builtin_amdgcn_fdot2_f32_bf16(q0, ones, ps0, false);
-      ps1 = __builtin_amdgcn_fdot2_f32_bf16(q1, ones, ps1, false);
-      pb[aa * 2 + (e >> 3)][e & 7] = q0[0];
-      pb[aa * 2 + (e >> 3)][(e & 7) + 1] = q0[1];
-      pb[aa * 2 + (e >> 3)][(e & 7) + 2] = q1[0];
-      pb[aa * 2 + (e >> 3)][(e & 7) + 3] = q1[1];
+      for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        s[0][e] -= shift;
+        s[1][e] -= shift;
+        neg_ref[e] = -ref_new;
+      }
+      moved = true;
     }
+    ps0 = 0.f;
+    ps1 = 0.f;
+#pragma unroll
+    for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+      for (int e = 0; e < 16; e += 4) {
+        const bf16x2 q0 = {(bf16_t)__builtin_amdgcn_exp2f(s[aa][e]), (bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 1])};
+        const bf16x2 q1 = {(bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 2]), (bf16_t)__builtin_amdgcn_exp2f(s[aa][e + 3])};
+        ps0 = __builtin_amdgcn_fdot2_f32_bf16(q0, ones, ps0, false);
+        ps1 = __builtin_amdgcn_fdot2_f32_bf16(q1, ones, ps1, false);
+        pb[aa * 2 + (e >> 3)][e & 7] = q0[0];
+        pb[aa * 2 + (e >> 3)][(e & 7) + 1] = q0[1];
+        pb[aa * 2 + (e >> 3)][(e & 7) + 2] = q1[0];
+        pb[aa * 2 + (e >> 3)][(e & 7) + 3] = q1[1];
+      }
+    if (moved) break;
+    move = __builtin_amdgcn_ballot_w64(!(ps0 + ps1 <= limit)) != 0;
+    if (!move) break;
+  }
   l_run += ps0 + ps1;
 }
 
