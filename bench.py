@@ -57,10 +57,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 #   mfma_util      SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES): share of the cycles a
 #                  busy CU's matrix pipes were busy
 PMC = {
-    "cfg3": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 544493601, "mfma_util": 0.586},
-    "cfg3_H4": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 494096390, "mfma_util": 0.576},
-    "cfg5": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 1052545778, "mfma_util": 0.531},
-    "cfg2": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 42194394, "mfma_util": 0.292},
+    "cfg3": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 551348019, "mfma_util": 0.573},
+    "cfg3_H4": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 499010453, "mfma_util": 0.563},
+    "cfg5": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 1165607648, "mfma_util": 0.517},
+    "cfg2": {"source": "profiles/hbm_traffic_pmc.txt, profiles/prefill_pmc_counters.txt", "traffic_bytes": 42180837, "mfma_util": 0.289},
     "decode": {"source": "profiles/hbm_traffic_pmc.txt", "traffic_bytes": 82282004},
 }
 
