@@ -29,6 +29,7 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units a row maximum may lag be
 #define FEDATTN_SGB_DS_READ 0x100
 
 
+
 // One direct-to-LDS load: every lane fetches 16 bytes from base + off (bytes) and the
 // wavefront's 1 KB lands at LDS byte address lds_addr (+16 per lane).  base and
 // lds_addr must be wave-uniform.  The instruction is written out so that the compiler
@@ -108,11 +109,9 @@ struct KvTile {
     if (VSWZ == 0) return (2 * (row & 7)) & (CPR - 1);
     return CPR >= 16 ? 4 * (row & 3) : 4 * ((row >> 1) & 1);
   }
-  int dma_row[IPW];        // tile row this lane fetches in its wave's i-th instruction
-  int dma_kcol[IPW];       // element offset of the K chunk inside the row
-  int dma_vcol[IPW];       // element offset of the V chunk inside the row
-  uint32_t dma_koff[IPW];  // byte offset from the tile's first row (full tiles)
-  uint32_t dma_voff[IPW];
+  uint32_t dma_koff[IPW];  // byte offset from the tile's first row of what this lane fetches in its
+  uint32_t dma_voff[IPW];  // wave's i-th instruction (full tiles; ragged tiles work theirs out on the spot)
+  int lane;
   // LDS -> MFMA A operand of S^T: lane (kv row 32 aa + l32, half hf) reads chunk
   // 2 st + hf of its row; k_off[st] is its swizzled byte offset (aa goes in the
   // instruction's immediate offset).
@@ -124,19 +123,27 @@ struct KvTile {
   int wave;
   int row_elems;           // elements between consecutive KV rows in HBM
 
-  __device__ __attribute__((always_inline)) void init(int lane, int wave_, int row_elems_) {
+  // tile row and element offset of the chunk inside the row that this lane fetches in its wave's i-th instruction
+  __device__ __attribute__((always_inline)) void dma_slot(int i, bool is_v, int& row, int& col) const {
+    const int sidx = (wave * IPW + i) * 64 + lane;
+    const int cp = sidx % CPR;
+    row = sidx / CPR;
+    col = (cp ^ (is_v ? v_swizzle(row) : (row & (CPR - 1)))) * 8;
+  }
+
+  __device__ __attribute__((always_inline)) void init(int lane_, int wave_, int row_elems_) {
+    const int lane = lane_;
+    this->lane = lane_;
     wave = wave_;
     row_elems = row_elems_;
     const int l32 = lane & 31, hf = lane >> 5;
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
-      const int sidx = (wave * IPW + i) * 64 + lane;
-      const int row = sidx / CPR, cp = sidx % CPR;
-      dma_row[i] = row;
-      dma_kcol[i] = (cp ^ (row & (CPR - 1))) * 8;
-      dma_vcol[i] = (cp ^ v_swizzle(row)) * 8;
-      dma_koff[i] = (uint32_t)(row * row_elems + dma_kcol[i]) * 2u;
-      dma_voff[i] = (uint32_t)(row * row_elems + dma_vcol[i]) * 2u;
+      int row, kcol, vcol;
+      dma_slot(i, false, row, kcol);
+      dma_slot(i, true, row, vcol);
+      dma_koff[i] = (uint32_t)(row * row_elems + kcol) * 2u;
+      dma_voff[i] = (uint32_t)(row * row_elems + vcol) * 2u;
     }
 #pragma unroll
     for (int st = 0; st < KSTEPS; ++st) k_off[st] = l32 * ROWB + (((2 * st + hf) ^ (l32 & (CPR - 1))) * 16);
@@ -160,8 +167,9 @@ struct KvTile {
     } else {
 #pragma unroll
       for (int i = 0; i < IPW; ++i) {
-        const uint32_t o2 =
-            (uint32_t)(min(dma_row[i], len - 1) * row_elems + (IS_V ? dma_vcol[i] : dma_kcol[i])) * 2u;
+        int row, col;
+        dma_slot(i, IS_V, row, col);
+        const uint32_t o2 = (uint32_t)(min(row, len - 1) * row_elems + col) * 2u;
         lds_dma_16<STREAM>(tile_base, o2, lds_stage + (wave * IPW + i) * 1024);
       }
     }
