@@ -91,6 +91,12 @@ FEDATTN_API size_t fedattn_workspace_bytes(const fedattn_params* params, int32_t
  *   Sparse KV exchange (adaptive KV aggregation): when keep_chunks is given,
  *   a sync block sees a remote participant's rows only in the chunks flagged 1;
  *   a participant's own rows are always complete.
+ *   Arithmetic: fp32 inputs in fp32 throughout.  bf16 inputs with D = 64 or 128: both products
+ *   on bf16 MFMA with fp32 accumulation, softmax in fp32, the weights rounded to bf16 for the
+ *   second product (the row sum is taken over the rounded weights); when the softmax scale does
+ *   not exceed 1/sqrt(D) it is folded into the query operand (q * scale * log2(e), rounded to
+ *   bf16), otherwise applied to the fp32 scores.  Other bf16 shapes: fp32 arithmetic on the
+ *   bf16 values.
  *
  *   block_idx      0-based block index; with sync_override = -1 the block is a sync
  *                  block iff fedattn_is_sync_block(params->sync_interval, block_idx).
