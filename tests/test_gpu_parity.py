@@ -512,6 +512,56 @@ def test_offsets_beyond_32_bits():
         check(host(od[:, h:h + 1]), ref, BF16, "2^20 cache rows, sync decode, head %d" % h)
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes_with_score_ramps(case):
+    """Seeded random layouts as above, with softmax scales on both sides of 1/sqrt(D) (the MFMA kernel folds
+    scales up to there into its Q operand) and, in three cases of four, scores that rise, fall or peak along
+    the sequence by 6 to 14 (log2 units) per 64 keys, so that the reference of the online softmax moves in
+    the middle of walks; dense local and sync blocks, or a sparse sync block."""
+    g = np.random.default_rng(52000 + case)
+    N = int(g.integers(1, 10))
+    lens = g.integers(0, int(g.choice([40, 200, 700, 1500])), size=N)
+    if lens.sum() == 0:
+        lens[0] = 33
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(seg[-1])
+    D = int(g.choice([64, 128]))
+    Hkv = int(g.choice([1, 2, 4]))
+    Hq = Hkv * int(g.choice([1, 2, 4, 8]))
+    causal = bool(g.random() < 0.7)
+    dflt = D ** -0.5
+    scale = float(g.choice([0.0, dflt * 0.5, dflt * 0.999, dflt * 1.001, dflt * 2.0]))
+    sigma = float(g.choice([0.5, 1.0]))
+    mk = lambda *s: (sigma * g.standard_normal(s)).astype(np.float32)
+    q, k, v = mk(total, Hq, D), mk(total, Hkv, D), mk(total, Hkv, D)
+    mode = int(g.integers(0, 4))
+    if mode:
+        u = g.standard_normal(D)
+        u /= np.linalg.norm(u)
+        sc = scale if scale else dflt
+        per_key = float(g.uniform(6, 14)) / 64.0 / (sc * np.log2(np.e))
+        pos = np.arange(total, dtype=np.float64)
+        span = float(g.choice([128, 320]))
+        ramp = {1: np.minimum(pos, span), 2: np.maximum(span - pos, 0.0),
+                3: np.maximum(span - np.abs(pos - total / 2), 0.0)}[mode]
+        q = q * 0.3 + (u[None, None, :] * 4.0).astype(np.float32)
+        k = k * 0.3 + (u[None, None, :] * (ramp * per_key / 4.0)[:, None, None]).astype(np.float32)
+    q, k, v = fi.round_to_bf16(q), fi.round_to_bf16(k), fi.round_to_bf16(v)
+    sparse = g.random() < 0.3
+    flags, chunk = None, 0
+    if sparse:
+        chunk = int(g.choice([1, 16, 64]))
+        flags = (g.random(int(fi.chunk_counts(np.diff(seg), chunk).sum())) < 0.5).astype(np.uint8)
+    for sync in ((1,) if sparse else (0, 1)):
+        say("ramp case %d: N=%d total=%d Hq=%d Hkv=%d D=%d causal=%d scale=%.4f mode=%d sparse=%d sync=%d"
+            % (case, N, total, Hq, Hkv, D, causal, scale, mode, sparse, sync))
+        got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, causal=causal, sync_override=sync,
+                      scale=scale, keep_chunks=flags, chunk_tokens=chunk)
+        ref = oracle.attend_block(q, k, v, seg, is_sync=bool(sync), causal=causal, scale=scale if scale else None,
+                                  keep_tok=oracle.expand_keep_chunks(flags, seg, chunk) if sparse else None)
+        check(got, ref, BF16, "ramp case %d sync=%d" % (case, sync))
+
+
 # --------------------------------------------------------------------- decode
 @pytest.mark.parametrize("N,Hq,Hkv,D,dtype", [(3, 8, 2, 128, BF16), (1, 4, 1, 128, BF16), (20, 8, 2, 128, BF16),
                                               (5, 6, 3, 64, BF16), (3, 4, 2, 64, F32), (2, 2, 1, 40, BF16)])
