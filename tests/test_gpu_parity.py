@@ -162,6 +162,25 @@ def test_mfma_prefill_scores_that_keep_outgrowing_the_reference(D, scale, trend)
             check(got, ref, BF16, "growing scores D=%d scale=%g %s causal=%d sync=%d" % (D, scale, trend, causal, sync))
 
 
+@pytest.mark.parametrize("D,Hkv", [(64, 1), (64, 2), (128, 1), (128, 2)])
+@pytest.mark.parametrize("scale", [0.0, 0.4])
+def test_mfma_prefill_few_long_walks(D, Hkv, scale):
+    """A grid of few workgroups whose walks are long (4 x 512 tokens, one or two KV heads, sync block): the
+    launch that splits every walk's KV tiles between the two halves of an 8-wave workgroup and merges the
+    halves at the end, at both head dimensions, with the folded scale and without; the local block of
+    the same layout (short walks, one tile per 4-wave workgroup) beside it.  Every row is checked."""
+    Hq = 4 * Hkv
+    seg = np.array([0, 512, 1024, 1536, 2048], dtype=np.int32)
+    q, k, v = rand_block(17, 2048, Hq, Hkv, D, sigma=0.7)
+    for causal in (True, False):
+        for sync in (1, 0):
+            say("few long walks D=%d Hkv=%d scale=%g causal=%d sync=%d" % (D, Hkv, scale, causal, sync))
+            got = prefill(q, k, v, seg, Hq=Hq, Hkv=Hkv, D=D, H=0, block=0, dtype=BF16, causal=causal,
+                          sync_override=sync, scale=scale)
+            ref = oracle.attend_block(q, k, v, seg, is_sync=bool(sync), causal=causal, scale=scale if scale else None)
+            check(got, ref, BF16, "few long walks D=%d Hkv=%d scale=%g causal=%d sync=%d" % (D, Hkv, scale, causal, sync))
+
+
 @pytest.mark.parametrize("chunk", [64, 128])
 def test_mfma_prefill_sparse_exchange(chunk):
     seg = np.array([0, 256, 256, 579, 900, 1001], dtype=np.int32)   # ragged last chunks
